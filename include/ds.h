@@ -1,0 +1,176 @@
+/*
+ * ds.h — C ABI of the MI355X (gfx950) prefill / KV-migrate / decode library.
+ *
+ * The library computes, for ONE transformer layer of an OPT-style decoder
+ * (pre-LayerNorm, ReLU FFN, multi-head attention; paper Sec. 6.1 / App. A):
+ *   - the prefill pass over packed prompts      (App. A.2: QKV, Attn-Output,
+ *     FFN-Input, FFN-Output GEMMs + per-request causal attention),
+ *   - the decode step over a paged KV cache     (App. A.3: the same four GEMMs
+ *     at B rows + one-query attention over the cached tokens),
+ *   - the KV hand-off from the prefill side's contiguous K/V to the decode
+ *     side's paged block layout                 (Sec. 3.3, Sec. 4.3 "pull").
+ * The caller loops over layers.  Symbols follow App. A.1: h hidden size,
+ * n heads, s head size (h = n*s), m FFN size, B batch, l_i lengths, t = sum l_i.
+ *
+ * Conventions that hold for every call:
+ *   - "device" pointers are HIP device memory, 16-byte aligned, caller-owned;
+ *     the library never allocates, frees or keeps them past the call.
+ *   - bf16 tensors are row-major; accumulation is fp32.
+ *   - Matrices are [out_features, in_features] (reduction dim contiguous).
+ *     w_qkv rows are [Q | K | V]; inside each third row = head*s + d.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream); no call synchronises; outputs are valid once the
+ *     caller has synchronised the stream.
+ *   - Errors are returned as ds_status; arguments are checked on the host
+ *     before anything is launched.  Contents of device index arrays
+ *     (cu_seqlens, block_tables, ctx_lens) are NOT validated: out-of-range
+ *     entries are the caller's responsibility.  ds_last_error() gives text.
+ *   - Paged cache layout: k_cache, v_cache [num_blocks, n, block_size, s] bf16.
+ *     Token j of sequence i lives in block block_tables[i*max_blocks + j/bs],
+ *     slot j % bs.  Unused table entries are -1 and never dereferenced.
+ */
+#ifndef DS_H_
+#define DS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DS_OK = 0,
+  DS_ERR_INVALID_ARG = 1, /* NULL / non-positive size / misaligned pointer / inconsistent sizes */
+  DS_ERR_UNSUPPORTED = 2, /* a shape this build has no kernel for */
+  DS_ERR_WORKSPACE = 3,   /* workspace smaller than ds_*_workspace_bytes() */
+  DS_ERR_HIP = 4          /* a HIP runtime call or launch failed */
+} ds_status;
+
+/* Layer dimensions.  Supported: head_dim in {64,128}; hidden = n_heads*head_dim;
+ * hidden and ffn multiples of 64; block_size = 16. */
+typedef struct {
+  int32_t hidden;     /* h */
+  int32_t n_heads;    /* n */
+  int32_t head_dim;   /* s */
+  int32_t ffn;        /* m */
+  int32_t block_size; /* tokens per KV page */
+  float ln_eps;       /* LayerNorm epsilon (biased variance, fp32 statistics) */
+} ds_model_cfg;
+
+/* One layer's parameters: device pointers to bf16.  Bias pointers may be NULL
+ * (= no bias).  LayerNorm gain/shift must be present. */
+typedef struct {
+  const void *ln1_g, *ln1_b;   /* [h] */
+  const void *w_qkv, *b_qkv;   /* [3h,h], [3h] */
+  const void *w_o, *b_o;       /* [h,h],  [h]  */
+  const void *ln2_g, *ln2_b;   /* [h] */
+  const void *w_fc1, *b_fc1;   /* [m,h],  [m]  */
+  const void *w_fc2, *b_fc2;   /* [h,m],  [h]  */
+} ds_layer_weights;
+
+typedef struct ds_ctx ds_ctx; /* opaque; owns no device memory */
+
+/* Create / destroy a context for one layer shape on the current HIP device. */
+ds_status ds_create(const ds_model_cfg *cfg, ds_ctx **out);
+void ds_destroy(ds_ctx *ctx);
+/* Text of the last error recorded on ctx (never NULL). */
+const char *ds_last_error(const ds_ctx *ctx);
+
+/* Workspace (device bytes) ds_prefill needs for up to max_tokens packed tokens. */
+size_t ds_prefill_workspace_bytes(const ds_ctx *ctx, int32_t max_tokens);
+/* Workspace ds_decode_step needs for up to max_batch sequences of up to max_ctx cached tokens. */
+size_t ds_decode_workspace_bytes(const ds_ctx *ctx, int32_t max_batch, int32_t max_ctx);
+
+/*
+ * Prefill (App. A.2): one layer over B packed prompts.
+ *   x          device [t,h] bf16, row r = token r of the packed batch
+ *   cu_seqlens device [B+1] int32, cu[0]=0, cu[B]=t (prompt i = rows cu[i]..cu[i+1]-1)
+ *   max_seqlen host upper bound of the prompt lengths (sizes the attention grid)
+ *   y          device [t,h] bf16 layer output; must not alias x
+ *   k_out,v_out device [t,n,s] bf16: this layer's K,V rows, contiguous per token
+ *              (what the prefill instance keeps until the decode side pulls it)
+ */
+ds_status ds_prefill(ds_ctx *ctx, const ds_layer_weights *w, const void *x,
+                     const int32_t *cu_seqlens, int32_t B, int32_t t, int32_t max_seqlen,
+                     void *y, void *k_out, void *v_out,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * KV hand-off (Sec. 3.3 / 4.3): scatter contiguous K,V rows of B prompts into
+ * the paged cache.  Pure byte copy (bit-exact).  Slots no token maps to, and
+ * blocks not named in block_tables, are left untouched.
+ *   k_src,v_src  device [t,n,s] bf16 (ds_prefill's k_out, v_out)
+ *   block_tables device [B,max_blocks_per_seq] int32
+ *   max_seqlen   host upper bound of the prompt lengths
+ */
+ds_status ds_kv_migrate(ds_ctx *ctx, const void *k_src, const void *v_src,
+                        const int32_t *cu_seqlens, int32_t B, int32_t t, int32_t max_seqlen,
+                        const int32_t *block_tables, int32_t max_blocks_per_seq,
+                        void *k_cache, void *v_cache, int32_t num_blocks, void *stream);
+
+/*
+ * Decode step (App. A.3): one new token for each of B sequences.
+ *   x        device [B,h] bf16 new-token activations
+ *   ctx_lens device [B] int32: tokens already cached BEFORE this step.  The new
+ *            token's K,V are appended at position ctx_lens[i] (its page must
+ *            already be present in block_tables) and the query attends over
+ *            ctx_lens[i]+1 keys.  The caller increments ctx_lens between steps.
+ *   max_ctx  host upper bound of ctx_lens[i]+1 (sizes the split of the KV axis)
+ *   y        device [B,h] bf16; must not alias x
+ */
+ds_status ds_decode_step(ds_ctx *ctx, const ds_layer_weights *w, const void *x,
+                         const int32_t *ctx_lens, const int32_t *block_tables,
+                         int32_t B, int32_t max_blocks_per_seq, int32_t max_ctx,
+                         void *k_cache, void *v_cache, int32_t num_blocks,
+                         void *y, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- the individual steps, exported for per-kernel parity tests and timing ---- */
+
+/* out[r,:] = LN(x[r,:]) * gamma + beta, rows x h bf16 (App. A: LayerNorm is a
+ * memory-bound op beside the GEMMs). */
+ds_status ds_layernorm(ds_ctx *ctx, const void *x, const void *gamma, const void *beta,
+                       int32_t rows, void *out, void *stream);
+
+/* y[rows,out_f] = act(x[rows,in_f] w[out_f,in_f]^T + bias) + residual   (GEMM tables
+ * of App. A.2 / A.3).  bias, residual may be NULL; relu != 0 applies max(0,.)
+ * before the residual.  in_f % 64 == 0, out_f % 8 == 0.  Rows <= 256 take the
+ * weight-streaming path of the decode phase and need `workspace` of
+ * ds_linear_workspace_bytes(); larger row counts take the MFMA tile path and
+ * ignore it. */
+size_t ds_linear_workspace_bytes(const ds_ctx *ctx, int32_t rows, int32_t in_f, int32_t out_f);
+ds_status ds_linear(ds_ctx *ctx, const void *x, const void *w, const void *bias,
+                    const void *residual, int32_t relu, int32_t rows, int32_t in_f, int32_t out_f,
+                    void *y, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Per-request causal attention over packed q,k,v [t,n,s] -> o [t,n,s] (App. A.2). */
+ds_status ds_prefill_attention(ds_ctx *ctx, const void *q, const void *k, const void *v,
+                               const int32_t *cu_seqlens, int32_t B, int32_t t, int32_t max_seqlen,
+                               void *o, void *stream);
+
+/* One-query attention over the paged cache: sequence i attends over its first
+ * kv_lens[i] cached tokens (App. A.3).  q,o device [B,n,s]; max_kv_len is a host
+ * bound of kv_lens; workspace of ds_decode_workspace_bytes(B, max_kv_len). */
+ds_status ds_decode_attention(ds_ctx *ctx, const void *q, const int32_t *kv_lens,
+                              const int32_t *block_tables, int32_t B, int32_t max_blocks_per_seq,
+                              int32_t max_kv_len, const void *k_cache, const void *v_cache,
+                              int32_t num_blocks, void *o,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- per-kernel timing (HIP events around every launch; off by default) ---- */
+enum {
+  DS_K_LAYERNORM = 0, DS_K_GEMM = 1, DS_K_PREFILL_ATTN = 2, DS_K_KV_MIGRATE = 3,
+  DS_K_SKINNY_GEMM = 4 /* incl. its split-K reduce */, DS_K_DECODE_ATTN = 5 /* incl. split merge */,
+  DS_K_KV_APPEND = 6, DS_K_COUNT = 7
+};
+/* Turn timing on/off.  When on, every launch is bracketed by events on the
+ * caller's stream (this serialises nothing, but adds event overhead). */
+ds_status ds_profile_enable(ds_ctx *ctx, int32_t on);
+/* Synchronise the recorded events, add their durations per kernel class into
+ * ms[DS_K_COUNT] / launches[DS_K_COUNT], and clear the record. */
+ds_status ds_profile_collect(ds_ctx *ctx, double *ms, int64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DS_H_ */

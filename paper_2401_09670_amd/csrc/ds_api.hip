@@ -1,0 +1,460 @@
+// C ABI of the library (declared in include/ds.h): argument checks on the
+// host, workspace carving, and the order in which the kernels of one layer
+// are enqueued.  No device memory is allocated here.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/ds.h"
+#include "kernels.h"
+
+struct ds_ctx {
+  ds_model_cfg cfg;
+  char err[512];
+  bool profile;
+  struct Rec {
+    int kind;
+    hipEvent_t a, b;
+  };
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> pool;
+};
+
+namespace {
+
+constexpr int kSkinnyMaxRows = 256;
+
+ds_status fail(ds_ctx* ctx, ds_status st, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return st;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Brackets one launcher call with events when profiling is on.
+struct Timed {
+  ds_ctx* ctx;
+  hipStream_t stream;
+  int kind;
+  hipEvent_t a = nullptr, b = nullptr;
+  Timed(ds_ctx* c, hipStream_t s, int k) : ctx(c), stream(s), kind(k) {
+    if (!ctx->profile) return;
+    a = take();
+    b = take();
+    if (a && b) (void)hipEventRecord(a, stream);
+  }
+  ~Timed() {
+    if (!ctx->profile || !a || !b) return;
+    (void)hipEventRecord(b, stream);
+    ctx->recs.push_back({kind, a, b});
+  }
+  hipEvent_t take() {
+    if (!ctx->pool.empty()) {
+      hipEvent_t e = ctx->pool.back();
+      ctx->pool.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+
+#define DS_LAUNCH(ctx, stream, kind, call)                                              \
+  do {                                                                                  \
+    hipError_t e_;                                                                      \
+    {                                                                                   \
+      Timed t_(ctx, stream, kind);                                                      \
+      e_ = (call);                                                                      \
+    }                                                                                   \
+    if (e_ != hipSuccess)                                                               \
+      return fail(ctx, DS_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_));      \
+  } while (0)
+
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+  void* take(size_t bytes) {
+    void* p = base ? base + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  }
+};
+
+// Y = act(X W^T + b) + residual for any row count: the weight-streaming kernel
+// for decode-sized batches, the MFMA tile kernel otherwise.
+bool use_skinny(int rows, int in_f) { return rows <= kSkinnyMaxRows && in_f % 128 == 0; }
+
+ds_status linear(ds_ctx* ctx, const void* x, const void* w, int rows, int in_f, int out_f,
+                 const ds::Epilogue& ep, void* skinny_ws, hipStream_t stream) {
+  if (use_skinny(rows, in_f)) {
+    hipError_t e;
+    {
+      Timed t(ctx, stream, DS_K_SKINNY_GEMM);
+      e = ds::launch_skinny_gemm(x, w, rows, out_f, in_f, ep, skinny_ws, stream);
+    }
+    if (e != hipSuccess) return fail(ctx, DS_ERR_HIP, "skinny gemm failed: %s", hipGetErrorString(e));
+    return DS_OK;
+  }
+  DS_LAUNCH(ctx, stream, DS_K_GEMM, ds::launch_gemm(x, w, rows, out_f, in_f, ep, stream));
+  return DS_OK;
+}
+
+size_t max_skinny_ws(const ds_model_cfg& c, int rows) {
+  size_t a = ds::skinny_workspace_bytes(rows, 3 * c.hidden, c.hidden);
+  size_t b = ds::skinny_workspace_bytes(rows, c.hidden, c.hidden);
+  size_t d = ds::skinny_workspace_bytes(rows, c.ffn, c.hidden);
+  size_t e = ds::skinny_workspace_bytes(rows, c.hidden, c.ffn);
+  size_t m = a > b ? a : b;
+  m = m > d ? m : d;
+  return m > e ? m : e;
+}
+
+ds_status check_weights(ds_ctx* ctx, const ds_layer_weights* w) {
+  if (!w) return fail(ctx, DS_ERR_INVALID_ARG, "weights is NULL");
+  const void* need[] = {w->ln1_g, w->ln1_b, w->w_qkv, w->w_o, w->ln2_g, w->ln2_b, w->w_fc1, w->w_fc2};
+  for (const void* p : need)
+    if (!p || !aligned16(p)) return fail(ctx, DS_ERR_INVALID_ARG, "a required weight pointer is NULL or misaligned");
+  const void* opt[] = {w->b_qkv, w->b_o, w->b_fc1, w->b_fc2};
+  for (const void* p : opt)
+    if (p && !aligned16(p)) return fail(ctx, DS_ERR_INVALID_ARG, "a bias pointer is misaligned");
+  return DS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ds_status ds_create(const ds_model_cfg* cfg, ds_ctx** out) {
+  if (!cfg || !out) return DS_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (cfg->hidden <= 0 || cfg->n_heads <= 0 || cfg->head_dim <= 0 || cfg->ffn <= 0) return DS_ERR_INVALID_ARG;
+  if (cfg->hidden != cfg->n_heads * cfg->head_dim) return DS_ERR_INVALID_ARG;
+  if (!(cfg->ln_eps > 0.f)) return DS_ERR_INVALID_ARG;
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return DS_ERR_UNSUPPORTED;
+  if (cfg->block_size != 16) return DS_ERR_UNSUPPORTED;
+  if (cfg->hidden % 64 != 0 || cfg->ffn % 64 != 0 || cfg->hidden > 16384) return DS_ERR_UNSUPPORTED;
+  ds_ctx* c = new (std::nothrow) ds_ctx();
+  if (!c) return DS_ERR_INVALID_ARG;
+  c->cfg = *cfg;
+  c->err[0] = 0;
+  c->profile = false;
+  *out = c;
+  return DS_OK;
+}
+
+void ds_destroy(ds_ctx* ctx) {
+  if (!ctx) return;
+  for (auto& r : ctx->recs) {
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  for (auto e : ctx->pool) (void)hipEventDestroy(e);
+  delete ctx;
+}
+
+const char* ds_last_error(const ds_ctx* ctx) { return ctx ? ctx->err : "ctx is NULL"; }
+
+size_t ds_prefill_workspace_bytes(const ds_ctx* ctx, int32_t max_tokens) {
+  if (!ctx || max_tokens <= 0) return 0;
+  const ds_model_cfg& c = ctx->cfg;
+  const size_t th = align_up((size_t)max_tokens * c.hidden * 2, 256);
+  const size_t tm = align_up((size_t)max_tokens * c.ffn * 2, 256);
+  // a (LN out, reused for LN2), q, o, x1, u, + skinny split-K partials for tiny batches
+  return 4 * th + tm + align_up(max_tokens <= kSkinnyMaxRows ? max_skinny_ws(c, max_tokens) : 0, 256);
+}
+
+size_t ds_decode_workspace_bytes(const ds_ctx* ctx, int32_t max_batch, int32_t max_ctx) {
+  if (!ctx || max_batch <= 0 || max_ctx <= 0) return 0;
+  const ds_model_cfg& c = ctx->cfg;
+  const size_t bh = align_up((size_t)max_batch * c.hidden * 2, 256);
+  const size_t b3h = align_up((size_t)max_batch * 3 * c.hidden * 2, 256);
+  const size_t bm = align_up((size_t)max_batch * c.ffn * 2, 256);
+  const size_t att = align_up(ds::decode_attention_workspace_bytes(max_batch, c.n_heads, c.head_dim, max_ctx), 256);
+  const size_t sk = align_up(max_batch <= kSkinnyMaxRows ? max_skinny_ws(c, max_batch) : 0, 256);
+  // a, qkv, o, x1, u, attention partials, split-K partials
+  return 3 * bh + b3h + bm + att + sk;
+}
+
+ds_status ds_layernorm(ds_ctx* ctx, const void* x, const void* gamma, const void* beta, int32_t rows,
+                       void* out, void* stream) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  if (!x || !gamma || !beta || !out || rows <= 0) return fail(ctx, DS_ERR_INVALID_ARG, "ds_layernorm: bad argument");
+  if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(out))
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_layernorm: pointers must be 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DS_LAUNCH(ctx, s, DS_K_LAYERNORM, ds::launch_layernorm(x, gamma, beta, out, rows, ctx->cfg.hidden, ctx->cfg.ln_eps, s));
+  return DS_OK;
+}
+
+size_t ds_linear_workspace_bytes(const ds_ctx* ctx, int32_t rows, int32_t in_f, int32_t out_f) {
+  if (!ctx || rows <= 0 || in_f <= 0 || out_f <= 0) return 0;
+  return use_skinny(rows, in_f) ? ds::skinny_workspace_bytes(rows, out_f, in_f) : 0;
+}
+
+ds_status ds_linear(ds_ctx* ctx, const void* x, const void* w, const void* bias, const void* residual,
+                    int32_t relu, int32_t rows, int32_t in_f, int32_t out_f, void* y, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  if (!x || !w || !y || rows <= 0 || in_f <= 0 || out_f <= 0)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_linear: NULL pointer or non-positive size");
+  if (in_f % 64 != 0 || out_f % 8 != 0)
+    return fail(ctx, DS_ERR_UNSUPPORTED, "ds_linear: in_f must be a multiple of 64 and out_f of 8");
+  if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(bias) || !aligned16(residual) ||
+      !aligned16(workspace))
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_linear: pointers must be 16-byte aligned");
+  const size_t need = ds_linear_workspace_bytes(ctx, rows, in_f, out_f);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return fail(ctx, DS_ERR_WORKSPACE, "ds_linear: workspace %zu < %zu", workspace_bytes, need);
+  ds::Epilogue ep;
+  ep.bias = bias;
+  ep.residual = residual;
+  ep.relu = relu;
+  ep.out[0] = y;
+  ep.seg_cols = out_f;
+  return linear(ctx, x, w, rows, in_f, out_f, ep, workspace, static_cast<hipStream_t>(stream));
+}
+
+ds_status ds_prefill_attention(ds_ctx* ctx, const void* q, const void* k, const void* v,
+                               const int32_t* cu_seqlens, int32_t B, int32_t t, int32_t max_seqlen, void* o,
+                               void* stream) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  if (!q || !k || !v || !o || !cu_seqlens || B <= 0 || t <= 0 || max_seqlen <= 0 || max_seqlen > t)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_prefill_attention: bad argument");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_prefill_attention: pointers must be 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DS_LAUNCH(ctx, s, DS_K_PREFILL_ATTN,
+            ds::launch_prefill_attention(q, k, v, cu_seqlens, B, max_seqlen, ctx->cfg.n_heads, ctx->cfg.head_dim, o, s));
+  return DS_OK;
+}
+
+ds_status ds_prefill(ds_ctx* ctx, const ds_layer_weights* w, const void* x, const int32_t* cu_seqlens,
+                     int32_t B, int32_t t, int32_t max_seqlen, void* y, void* k_out, void* v_out,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  ds_status st = check_weights(ctx, w);
+  if (st != DS_OK) return st;
+  if (!x || !cu_seqlens || !y || !k_out || !v_out)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_prefill: NULL pointer");
+  if (B <= 0 || t <= 0 || max_seqlen <= 0 || max_seqlen > t || B > t)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_prefill: need B>0, t>0, 0<max_seqlen<=t, B<=t");
+  if (x == y) return fail(ctx, DS_ERR_INVALID_ARG, "ds_prefill: y must not alias x");
+  if (!aligned16(x) || !aligned16(y) || !aligned16(k_out) || !aligned16(v_out) || !aligned16(workspace))
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_prefill: pointers must be 16-byte aligned");
+  const size_t need = ds_prefill_workspace_bytes(ctx, t);
+  if (!workspace || workspace_bytes < need)
+    return fail(ctx, DS_ERR_WORKSPACE, "ds_prefill: workspace %zu < %zu", workspace_bytes, need);
+
+  const ds_model_cfg& c = ctx->cfg;
+  const int h = c.hidden, m = c.ffn;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Carver ws(workspace);
+  void* a = ws.take((size_t)t * h * 2);
+  void* q = ws.take((size_t)t * h * 2);
+  void* o = ws.take((size_t)t * h * 2);
+  void* x1 = ws.take((size_t)t * h * 2);
+  void* u = ws.take((size_t)t * m * 2);
+  void* sk = ws.take(0);
+
+  // a = LN1(x)
+  DS_LAUNCH(ctx, s, DS_K_LAYERNORM, ds::launch_layernorm(x, w->ln1_g, w->ln1_b, a, t, h, c.ln_eps, s));
+  // [q | k_out | v_out] = a W_qkv^T + b_qkv
+  {
+    ds::Epilogue ep;
+    ep.bias = w->b_qkv;
+    ep.out[0] = q; ep.out[1] = k_out; ep.out[2] = v_out;
+    ep.seg_cols = h;
+    st = linear(ctx, a, w->w_qkv, t, h, 3 * h, ep, sk, s);
+    if (st != DS_OK) return st;
+  }
+  // o = causal attention per request
+  DS_LAUNCH(ctx, s, DS_K_PREFILL_ATTN,
+            ds::launch_prefill_attention(q, k_out, v_out, cu_seqlens, B, max_seqlen, c.n_heads, c.head_dim, o, s));
+  // x1 = x + o W_o^T + b_o
+  {
+    ds::Epilogue ep;
+    ep.bias = w->b_o; ep.residual = x;
+    ep.out[0] = x1; ep.seg_cols = h;
+    st = linear(ctx, o, w->w_o, t, h, h, ep, sk, s);
+    if (st != DS_OK) return st;
+  }
+  // f = LN2(x1) (reuses a)
+  DS_LAUNCH(ctx, s, DS_K_LAYERNORM, ds::launch_layernorm(x1, w->ln2_g, w->ln2_b, a, t, h, c.ln_eps, s));
+  // u = relu(f W_1^T + b_1)
+  {
+    ds::Epilogue ep;
+    ep.bias = w->b_fc1; ep.relu = 1;
+    ep.out[0] = u; ep.seg_cols = m;
+    st = linear(ctx, a, w->w_fc1, t, h, m, ep, sk, s);
+    if (st != DS_OK) return st;
+  }
+  // y = x1 + u W_2^T + b_2
+  {
+    ds::Epilogue ep;
+    ep.bias = w->b_fc2; ep.residual = x1;
+    ep.out[0] = y; ep.seg_cols = h;
+    st = linear(ctx, u, w->w_fc2, t, m, h, ep, sk, s);
+    if (st != DS_OK) return st;
+  }
+  return DS_OK;
+}
+
+ds_status ds_kv_migrate(ds_ctx* ctx, const void* k_src, const void* v_src, const int32_t* cu_seqlens,
+                        int32_t B, int32_t t, int32_t max_seqlen, const int32_t* block_tables,
+                        int32_t max_blocks_per_seq, void* k_cache, void* v_cache, int32_t num_blocks,
+                        void* stream) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  if (!k_src || !v_src || !cu_seqlens || !block_tables || !k_cache || !v_cache)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_kv_migrate: NULL pointer");
+  if (B <= 0 || t <= 0 || max_seqlen <= 0 || max_seqlen > t || num_blocks <= 0 || max_blocks_per_seq <= 0)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_kv_migrate: non-positive or inconsistent size");
+  if ((int64_t)max_blocks_per_seq * ctx->cfg.block_size < max_seqlen)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_kv_migrate: max_seqlen %d does not fit %d blocks per sequence",
+                max_seqlen, max_blocks_per_seq);
+  if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(k_cache) || !aligned16(v_cache))
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_kv_migrate: pointers must be 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DS_LAUNCH(ctx, s, DS_K_KV_MIGRATE,
+            ds::launch_kv_migrate(k_src, v_src, cu_seqlens, B, max_seqlen, block_tables, max_blocks_per_seq,
+                                  k_cache, v_cache, ctx->cfg.n_heads, ctx->cfg.head_dim, s));
+  return DS_OK;
+}
+
+ds_status ds_decode_attention(ds_ctx* ctx, const void* q, const int32_t* kv_lens, const int32_t* block_tables,
+                              int32_t B, int32_t max_blocks_per_seq, int32_t max_kv_len, const void* k_cache,
+                              const void* v_cache, int32_t num_blocks, void* o, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  if (!q || !kv_lens || !block_tables || !k_cache || !v_cache || !o)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_decode_attention: NULL pointer");
+  if (B <= 0 || max_kv_len <= 0 || num_blocks <= 0 || max_blocks_per_seq <= 0 ||
+      (int64_t)max_blocks_per_seq * ctx->cfg.block_size < max_kv_len)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_decode_attention: non-positive or inconsistent size");
+  if (!aligned16(q) || !aligned16(o) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(workspace))
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_decode_attention: pointers must be 16-byte aligned");
+  const ds_model_cfg& c = ctx->cfg;
+  const size_t need = ds::decode_attention_workspace_bytes(B, c.n_heads, c.head_dim, max_kv_len);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return fail(ctx, DS_ERR_WORKSPACE, "ds_decode_attention: workspace %zu < %zu", workspace_bytes, need);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DS_LAUNCH(ctx, s, DS_K_DECODE_ATTN,
+            ds::launch_decode_attention(q, c.hidden, kv_lens, 0, block_tables, B, max_blocks_per_seq, max_kv_len,
+                                        k_cache, v_cache, c.n_heads, c.head_dim, o, workspace, s));
+  return DS_OK;
+}
+
+ds_status ds_decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, const int32_t* ctx_lens,
+                         const int32_t* block_tables, int32_t B, int32_t max_blocks_per_seq, int32_t max_ctx,
+                         void* k_cache, void* v_cache, int32_t num_blocks, void* y, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  ds_status st = check_weights(ctx, w);
+  if (st != DS_OK) return st;
+  if (!x || !ctx_lens || !block_tables || !k_cache || !v_cache || !y)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_decode_step: NULL pointer");
+  if (B <= 0 || max_ctx <= 0 || num_blocks <= 0 || max_blocks_per_seq <= 0)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_decode_step: non-positive size");
+  if ((int64_t)max_blocks_per_seq * ctx->cfg.block_size < max_ctx)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_decode_step: max_ctx %d does not fit %d blocks per sequence", max_ctx,
+                max_blocks_per_seq);
+  if (x == y) return fail(ctx, DS_ERR_INVALID_ARG, "ds_decode_step: y must not alias x");
+  if (!aligned16(x) || !aligned16(y) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(workspace))
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_decode_step: pointers must be 16-byte aligned");
+  const size_t need = ds_decode_workspace_bytes(ctx, B, max_ctx);
+  if (!workspace || workspace_bytes < need)
+    return fail(ctx, DS_ERR_WORKSPACE, "ds_decode_step: workspace %zu < %zu", workspace_bytes, need);
+
+  const ds_model_cfg& c = ctx->cfg;
+  const int h = c.hidden, m = c.ffn;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Carver ws(workspace);
+  void* a = ws.take((size_t)B * h * 2);
+  void* o = ws.take((size_t)B * h * 2);
+  void* x1 = ws.take((size_t)B * h * 2);
+  void* qkv = ws.take((size_t)B * 3 * h * 2);
+  void* u = ws.take((size_t)B * m * 2);
+  void* att = ws.take(ds::decode_attention_workspace_bytes(B, c.n_heads, c.head_dim, max_ctx));
+  void* sk = ws.take(0);
+
+  DS_LAUNCH(ctx, s, DS_K_LAYERNORM, ds::launch_layernorm(x, w->ln1_g, w->ln1_b, a, B, h, c.ln_eps, s));
+  {
+    ds::Epilogue ep;
+    ep.bias = w->b_qkv;
+    ep.out[0] = qkv; ep.seg_cols = 3 * h;
+    st = linear(ctx, a, w->w_qkv, B, h, 3 * h, ep, sk, s);
+    if (st != DS_OK) return st;
+  }
+  const uint16_t* qkv16 = static_cast<const uint16_t*>(qkv);
+  DS_LAUNCH(ctx, s, DS_K_KV_APPEND,
+            ds::launch_kv_append(qkv16 + h, qkv16 + 2 * h, 3 * h, ctx_lens, block_tables, B, max_blocks_per_seq,
+                                 k_cache, v_cache, c.n_heads, c.head_dim, s));
+  DS_LAUNCH(ctx, s, DS_K_DECODE_ATTN,
+            ds::launch_decode_attention(qkv, 3 * h, ctx_lens, 1, block_tables, B, max_blocks_per_seq, max_ctx,
+                                        k_cache, v_cache, c.n_heads, c.head_dim, o, att, s));
+  {
+    ds::Epilogue ep;
+    ep.bias = w->b_o; ep.residual = x;
+    ep.out[0] = x1; ep.seg_cols = h;
+    st = linear(ctx, o, w->w_o, B, h, h, ep, sk, s);
+    if (st != DS_OK) return st;
+  }
+  DS_LAUNCH(ctx, s, DS_K_LAYERNORM, ds::launch_layernorm(x1, w->ln2_g, w->ln2_b, a, B, h, c.ln_eps, s));
+  {
+    ds::Epilogue ep;
+    ep.bias = w->b_fc1; ep.relu = 1;
+    ep.out[0] = u; ep.seg_cols = m;
+    st = linear(ctx, a, w->w_fc1, B, h, m, ep, sk, s);
+    if (st != DS_OK) return st;
+  }
+  {
+    ds::Epilogue ep;
+    ep.bias = w->b_fc2; ep.residual = x1;
+    ep.out[0] = y; ep.seg_cols = h;
+    st = linear(ctx, u, w->w_fc2, B, m, h, ep, sk, s);
+    if (st != DS_OK) return st;
+  }
+  return DS_OK;
+}
+
+ds_status ds_profile_enable(ds_ctx* ctx, int32_t on) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  ctx->profile = on != 0;
+  return DS_OK;
+}
+
+ds_status ds_profile_collect(ds_ctx* ctx, double* ms, int64_t* launches) {
+  if (!ctx || !ms || !launches) return DS_ERR_INVALID_ARG;
+  for (int i = 0; i < DS_K_COUNT; ++i) {
+    ms[i] = 0.0;
+    launches[i] = 0;
+  }
+  for (auto& r : ctx->recs) {
+    hipError_t e = hipEventSynchronize(r.b);
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.a, r.b);
+    if (e != hipSuccess) return fail(ctx, DS_ERR_HIP, "event timing failed: %s", hipGetErrorString(e));
+    if (r.kind >= 0 && r.kind < DS_K_COUNT) {
+      ms[r.kind] += t;
+      launches[r.kind] += 1;
+    }
+    ctx->pool.push_back(r.a);
+    ctx->pool.push_back(r.b);
+  }
+  ctx->recs.clear();
+  return DS_OK;
+}
+
+}  // extern "C"

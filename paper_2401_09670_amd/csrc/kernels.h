@@ -1,0 +1,59 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher checks nothing
+// about pointer validity (the C ABI layer does) and enqueues on `stream`.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ds {
+
+// y = LN(x) * gamma + beta, one workgroup per row.  h % 8 == 0, h <= 16384.
+hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* out,
+                            int rows, int h, float eps, hipStream_t stream);
+
+// Epilogue of both GEMM paths: out = act(acc + bias) + residual, written as bf16.
+// The N output columns may be cut into up to three equal segments of
+// `seg_cols` columns that go to different buffers (Q | K | V); residual is
+// only allowed with a single segment.
+struct Epilogue {
+  const void* bias = nullptr;      // [N] bf16 or null
+  const void* residual = nullptr;  // [M, N] bf16 or null
+  int relu = 0;
+  void* out[3] = {nullptr, nullptr, nullptr};
+  int seg_cols = 0;  // N / number of segments; row stride of each out buffer
+};
+
+// Y[M,N] = X[M,K] W[N,K]^T (+ epilogue): MFMA tile kernel for large M (prefill).
+hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
+                       hipStream_t stream);
+
+// Same contraction for M <= 256 (decode): weights are streamed once from HBM.
+size_t skinny_workspace_bytes(int M, int N, int K);
+hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
+                              void* workspace, hipStream_t stream);
+
+// Causal attention within each packed request; q,k,v,o rows have `n_heads*head_dim` elements.
+hipError_t launch_prefill_attention(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                                    int B, int max_seqlen, int n_heads, int head_dim, void* o,
+                                    hipStream_t stream);
+
+// contiguous [t,n,s] -> paged [num_blocks,n,16,s] for K and V in one launch
+hipError_t launch_kv_migrate(const void* k_src, const void* v_src, const int32_t* cu_seqlens, int B,
+                             int max_seqlen, const int32_t* block_tables, int max_blocks, void* k_cache,
+                             void* v_cache, int n_heads, int head_dim, hipStream_t stream);
+
+// new K,V rows (row stride `src_stride` elements) of B sequences -> slot ctx_lens[i] of the paged cache
+hipError_t launch_kv_append(const void* k_new, const void* v_new, int src_stride, const int32_t* ctx_lens,
+                            const int32_t* block_tables, int B, int max_blocks, void* k_cache, void* v_cache,
+                            int n_heads, int head_dim, hipStream_t stream);
+
+// One query per (sequence, head) over the paged cache.  kv_len_add is added to
+// kv_lens[i] (1 when kv_lens holds the lengths before this step's append).
+size_t decode_attention_workspace_bytes(int B, int n_heads, int head_dim, int max_kv_len);
+int decode_attention_splits(int B, int n_heads, int max_kv_len);
+hipError_t launch_decode_attention(const void* q, int q_stride, const int32_t* kv_lens, int kv_len_add,
+                                   const int32_t* block_tables, int B, int max_blocks, int max_kv_len,
+                                   const void* k_cache, const void* v_cache, int n_heads, int head_dim,
+                                   void* o, void* workspace, hipStream_t stream);
+
+}  // namespace ds

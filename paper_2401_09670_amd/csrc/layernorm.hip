@@ -1,0 +1,88 @@
+// LayerNorm over the hidden dimension, bf16 in/out, fp32 statistics.
+// One 256-thread workgroup per row; the row stays in registers between the
+// mean, variance and normalise passes, so HBM sees one read and one write.
+#include "common.h"
+#include "kernels.h"
+
+namespace ds {
+
+constexpr int kLnThreads = 256;
+constexpr int kLnMaxChunks = 8;  // 8 chunks x 8 elements x 256 threads = 16384 elements per row
+
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int wave = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* __restrict__ x,
+                                                               const uint16_t* __restrict__ gamma,
+                                                               const uint16_t* __restrict__ beta,
+                                                               uint16_t* __restrict__ out, int h, float eps) {
+  __shared__ float red[4];
+  const int nchunk = h >> 3;
+  const size_t row = blockIdx.x;
+  const uint16_t* xr = x + row * (size_t)h;
+  uint16_t* orow = out + row * (size_t)h;
+
+  float vals[kLnMaxChunks][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < kLnMaxChunks; ++i) {
+    const int c = threadIdx.x + i * kLnThreads;
+    if (c < nchunk) {
+      const u32x4 raw = ld16(xr + c * 8);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        vals[i][2 * j] = bf16_lo(raw[j]);
+        vals[i][2 * j + 1] = bf16_hi(raw[j]);
+        sum += vals[i][2 * j] + vals[i][2 * j + 1];
+      }
+    }
+  }
+  const float mean = block_sum(sum, red) / (float)h;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < kLnMaxChunks; ++i) {
+    const int c = threadIdx.x + i * kLnThreads;
+    if (c < nchunk) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float d = vals[i][j] - mean;
+        sq += d * d;
+      }
+    }
+  }
+  const float var = block_sum(sq, red) / (float)h;
+  const float rstd = rsqrtf(var + eps);
+#pragma unroll
+  for (int i = 0; i < kLnMaxChunks; ++i) {
+    const int c = threadIdx.x + i * kLnThreads;
+    if (c < nchunk) {
+      const u32x4 g = ld16(gamma + c * 8);
+      const u32x4 b = ld16(beta + c * 8);
+      u32x4 o;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float lo = (vals[i][2 * j] - mean) * rstd * bf16_lo(g[j]) + bf16_lo(b[j]);
+        const float hi = (vals[i][2 * j + 1] - mean) * rstd * bf16_hi(g[j]) + bf16_hi(b[j]);
+        o[j] = pack_bf16(lo, hi);
+      }
+      st16(orow + c * 8, o);
+    }
+  }
+}
+
+hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* out, int rows, int h,
+                            float eps, hipStream_t stream) {
+  if (rows <= 0) return hipSuccess;
+  if (h % 8 != 0 || h > kLnThreads * 8 * kLnMaxChunks) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(layernorm_kernel, dim3(rows), dim3(kLnThreads), 0, stream, (const uint16_t*)x,
+                     (const uint16_t*)gamma, (const uint16_t*)beta, (uint16_t*)out, h, eps);
+  return hipGetLastError();
+}
+
+}  // namespace ds

@@ -1,0 +1,70 @@
+"""The C-ABI library loads and exports what include/ds.h declares; host-side
+argument checks work without a GPU (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2401_09670_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ds.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ds_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_all_exported():
+    lib = binding.load_library()
+    syms = declared_symbols()
+    assert set(syms) == set(binding.EXPORTS)
+    for s in syms:
+        assert hasattr(lib, s), s
+
+
+def test_create_validates_config():
+    lib = binding.load_library()
+    h = ctypes.c_void_p()
+    bad = [dict(hidden=256, n_heads=4, head_dim=32, ffn=1024, block_size=16, ln_eps=1e-5),   # head_dim
+           dict(hidden=256, n_heads=4, head_dim=64, ffn=1024, block_size=32, ln_eps=1e-5),   # page size
+           dict(hidden=250, n_heads=4, head_dim=64, ffn=1024, block_size=16, ln_eps=1e-5),   # h != n*s
+           dict(hidden=256, n_heads=4, head_dim=64, ffn=1000, block_size=16, ln_eps=1e-5),   # ffn % 64
+           dict(hidden=256, n_heads=4, head_dim=64, ffn=1024, block_size=16, ln_eps=0.0)]
+    for kw in bad:
+        cfg = binding.ModelCfg(**kw)
+        assert lib.ds_create(ctypes.byref(cfg), ctypes.byref(h)) != binding.DS_OK
+        assert not h.value
+    assert lib.ds_create(None, ctypes.byref(h)) == 1
+
+
+def test_host_argument_checks_return_status():
+    ctx = binding.Context(256, 4, 64, 1024)
+    assert ctx.ds_prefill_workspace_bytes(64) > 0
+    assert ctx.ds_decode_workspace_bytes(2, 48) > 0
+    assert ctx.ds_prefill_workspace_bytes(0) == 0
+    lib = ctx.lib
+    # NULL pointers are rejected before anything touches the device
+    st = lib.ds_kv_migrate(ctx.handle, None, None, None, 1, 16, 16, None, 1, None, None, 4, None)
+    assert st == 1 and b"NULL" in lib.ds_last_error(ctx.handle)
+    st = lib.ds_layernorm(ctx.handle, None, None, None, 4, None, None)
+    assert st == 1
+    lw = binding.LayerWeights()
+    st = lib.ds_prefill(ctx.handle, ctypes.byref(lw), None, None, 1, 16, 16, None, None, None, None, 0, None)
+    assert st == 1
+    # inconsistent sizes: 3 blocks of 16 cannot hold 64 tokens
+    st = lib.ds_kv_migrate(ctx.handle, 16, 16, 16, 1, 64, 64, 16, 3, 16, 16, 8, None)
+    assert st == 1 and b"does not fit" in lib.ds_last_error(ctx.handle)
+    # misaligned pointer
+    st = lib.ds_kv_migrate(ctx.handle, 8, 16, 16, 1, 64, 64, 16, 4, 16, 16, 8, None)
+    assert st == 1 and b"aligned" in lib.ds_last_error(ctx.handle)
+    ctx.close()
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libds.so")
+    with pytest.raises(RuntimeError):
+        binding.Context(256, 4, 64, 1024)
