@@ -40,3 +40,12 @@ def make_ctx(shape) -> binding.Context:
 
 def workspace(nbytes: int) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+def update_ok(y_gpu: np.ndarray, y_ref: np.ndarray, x_in: np.ndarray) -> bool:
+    """Gate on the layer's own contribution y - x (the residual input dominates y, so this is the
+    sharper check of attention + FFN).  The residual stream is rounded to bf16 twice on the GPU
+    (x1 and y), each within 2^-9 of its magnitude; on top of that the update gets the 1e-2 budget."""
+    upd_ref = y_ref - x_in
+    bound = 2 * 2.0 ** -9 * np.max(np.abs(y_ref)) + 1e-2 * np.max(np.abs(upd_ref))
+    return bool(np.max(np.abs((y_gpu - x_in) - upd_ref)) <= bound)

@@ -209,6 +209,8 @@ def test_config1_whole_path_every_element(gpu):
     y, k, v = orc.layer_prefill(w, orc.from_bf16_bits(xbits), lens, shape.n_heads)
     t = sum(lens)
     assert gu.rel_err(got["y"], y) < TOL
+    xin = orc.from_bf16_bits(xbits)          # the residual input dominates y: also gate the layer's own update
+    assert gu.update_ok(got["y"], y, xin)
     assert gu.rel_err(got["k"], k.reshape(t, -1)) < TOL
     assert gu.rel_err(got["v"], v.reshape(t, -1)) < TOL
     # decode: the oracle keeps its own fp64 cache, started from its own prefill K,V
@@ -217,8 +219,10 @@ def test_config1_whole_path_every_element(gpu):
     orc.kv_migrate(k, v, lens, got["bt"], kc, vc)
     ctx_lens = list(lens)
     for step in range(steps):
-        yr = orc.layer_decode_cached(w, orc.from_bf16_bits(dx[step]), ctx_lens, got["bt"], kc, vc, shape.n_heads)
+        xd = orc.from_bf16_bits(dx[step])
+        yr = orc.layer_decode_cached(w, xd, ctx_lens, got["bt"], kc, vc, shape.n_heads)
         assert gu.rel_err(got["decode"][step], yr) < TOL, step
+        assert gu.update_ok(got["decode"][step], yr, xd), step
         ctx_lens = [c + 1 for c in ctx_lens]
     # the GPU cache after the run: prefill rows are bit-identical to k_out/v_out, appended rows match the oracle
     kc_bits = np.zeros((got["nblk"], shape.n_heads, 16, shape.head_dim), dtype=np.uint16)
