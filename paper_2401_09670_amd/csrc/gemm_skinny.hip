@@ -1,27 +1,33 @@
 // Decode-phase GEMM: Y[M,N] = act(X[M,K] W[N,K]^T + bias) + residual, M <= 256.
 // The weights (N*K*2 bytes) are read once from HBM and dominate the traffic
 // (App. A.3: 4h^2 + 2hm elements per layer), so the kernel is organised
-// around streaming W: every wave pulls its own 16 weight rows straight from
-// global memory into MFMA fragments (no LDS hop for the big operand), while
-// the small activation slab X[:, k..k+128) is staged once per workgroup in LDS
-// and shared by the four waves.
+// around streaming W at HBM rate while the matrix cores do the M x ... work.
 //
-// grid = (N/64, KSPLIT).  Workgroup = 4 waves; wave w owns weight rows
-// n0+16w .. n0+16w+15 and all M activation rows (M/16 MFMA 16x16x32 tiles).
-// The tile is computed transposed (weights as MFMA row operand), so a lane
-// ends up with 4 consecutive output columns of one row.  With KSPLIT > 1 each
-// split writes fp32 partial sums and a second kernel reduces them in a fixed
-// order and applies the epilogue.
+// What bounds it on this chip is the number of bytes a CU can pull through
+// its vector L1 per unit time, and the activation slabs count against that
+// budget although they come from L2.  A workgroup therefore covers BN = 64,
+// 128 or 256 weight rows (the X slab is fetched once per BN columns), and the
+// K axis is split over workgroups until the chip is full; the launcher picks
+// BN and the split count that minimise weight + activation + partial-sum
+// bytes.
+//
+// grid = (N/BN, KSPLIT).  Workgroup = 8 waves: wave w owns the column tiles
+// (16 weight rows each) of column group w & 3 and, of every 128-wide k slab,
+// the two 32-wide MFMA k-steps 2*(w>>2), 2*(w>>2)+1; the two k-halves are
+// added through LDS at the end.  Both operands go global -> LDS directly (no
+// registers, no ds_write) into a ring of S stages; a wave-level load fetches
+// 4 rows x 256 contiguous bytes.  The tile is computed transposed (weights
+// as MFMA row operand), so a lane ends up with 4 consecutive output columns
+// of one row.  With KSPLIT > 1 each split writes fp32 partial sums and a
+// second kernel adds them in a fixed order and applies the epilogue.
 #include "common.h"
 #include "kernels.h"
 
 namespace ds {
 
-constexpr int kSkThreads = 256;
-constexpr int kSkBN = 64;                 // weight rows per workgroup
-constexpr int kSkKS = 128;                // k elements per slab
-constexpr int kSkXStride = kSkKS + 8;     // LDS row stride (272 B) for conflict-free 16-byte reads
-constexpr int kSkSteps = kSkKS / 32;      // MFMA k-steps per slab
+constexpr int kSkThreads = 512;
+constexpr int kSkWaves = kSkThreads / 64;
+constexpr int kSkKS = 128;  // k elements per slab
 
 struct SkinnyParams {
   const uint16_t* X;
@@ -32,120 +38,159 @@ struct SkinnyParams {
   int seg_cols;
   int M, N, K;
   int relu;
-  int slabs_per_split;
   float* partial;  // [KSPLIT][M][N] fp32 when gridDim.y > 1
 };
 
-template <int MT>  // activation row tiles of 16
+template <int VM>
+__device__ __forceinline__ void sk_wait_vmcnt() {
+  // s_waitcnt with only vmcnt set: vmcnt[3:0] | expcnt=7 | lgkmcnt=15 | vmcnt[5:4] in bits 15:14
+  __builtin_amdgcn_s_waitcnt((VM & 0xf) | (0x7 << 4) | (0xf << 8) | ((VM >> 4) << 14));
+}
+
+// MT = activation row tiles of 16 (4, 8, 16); NTW = column tiles per wave (1, 2, 4: BN = 64 * NTW);
+// S = LDS stages (prefetch distance D = S - 1).
+//
+// Stage layout: [MP rows of X | BN rows of W], every row 128 k-elements = 256 B = 16 chunks of
+// 16 B, unpadded; chunk c of row r sits at position c ^ (r & 15), so the 16 consecutive rows a
+// fragment read touches fall into 16 different bank groups.  The swizzle is applied on the global
+// side: lane l of a wave-level load fetches row 4g + l/16, chunk (l%16) ^ (row & 15).
+template <int MT, int NTW, int S>
 __global__ __launch_bounds__(kSkThreads) void skinny_gemm_kernel(const SkinnyParams p) {
-  constexpr int MP = MT * 16;                       // padded rows held in LDS
-  constexpr int XCH = MP * (kSkKS / 8) / kSkThreads;  // 16-byte chunks per thread per slab (= MT)
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];  // [2][MP][kSkXStride]
+  constexpr int MP = MT * 16;   // padded activation rows held in LDS
+  constexpr int BN = 64 * NTW;  // weight rows per workgroup
+  constexpr int D = S - 1;      // slabs in flight ahead of the one being multiplied
+  constexpr int STAGE_ELEMS = (MP + BN) * kSkKS;
+  constexpr int GROUPS = (MP + BN) / 4;  // wave-level loads (4 rows each) per slab
+  static_assert(GROUPS % kSkWaves == 0, "every wave issues the same number of loads");
+  constexpr int G = GROUPS / kSkWaves;  // loads per wave per slab
+  static_assert(D >= 1 && (D - 1) * G < 64, "vmcnt range");
+  extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];  // [S][MP + BN][128]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n0 = blockIdx.x * kSkBN;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int ng = wave & 3, kh = wave >> 2;  // column group, k half
+  const int n0 = blockIdx.x * BN;
   const int split = blockIdx.y;
+  const int n_splits = gridDim.y;
+  // The K axis is dealt to the splits slab by slab (split s takes slabs s, s + KSPLIT, ...).
   const int slabs_total = p.K / kSkKS;
-  const int slab_lo = split * p.slabs_per_split;
-  const int slab_hi = min(slabs_total, slab_lo + p.slabs_per_split);
-  const int ns = slab_hi - slab_lo;
+  const int ns = (slabs_total - split + n_splits - 1) / n_splits;  // >= 1: n_splits <= slabs_total
   const int K = p.K;
 
-  uint32_t xoff[XCH], xlds[XCH];
+  // load j of this wave is row group g = j*8 + wave of the stage (4 rows): X rows first, then W rows
+  const int lr = lane >> 4;
+  const uint16_t* src[G];
 #pragma unroll
-  for (int i = 0; i < XCH; ++i) {
-    const int c = tid + i * kSkThreads;
-    const int r = c >> 4, kc = c & 15;
-    xoff[i] = (uint32_t)min(r, p.M - 1) * (uint32_t)K + kc * 8;
-    xlds[i] = r * kSkXStride + kc * 8;
+  for (int j = 0; j < G; ++j) {
+    const int r = 4 * (j * kSkWaves + wave) + lr;  // stage row
+    const int sw = ((lane & 15) ^ (r & 15)) * 8;
+    if (r < MP) src[j] = p.X + (size_t)min(r, p.M - 1) * K + (size_t)split * kSkKS + sw;
+    else src[j] = p.W + (size_t)min(n0 + r - MP, p.N - 1) * K + (size_t)split * kSkKS + sw;
   }
-  const int wrow = min(n0 + wave * 16 + (lane & 15), p.N - 1);
-  const uint16_t* Wp = p.W + (size_t)wrow * K + (size_t)slab_lo * kSkKS + (lane >> 4) * 8;
-  const uint16_t* Xp = p.X + (size_t)slab_lo * kSkKS;
-
-  floatx4 acc[MT];
+  // requests slab i (clamped to the last real slab: a harmless re-load) into stage `st`
+  auto request = [&](int i, int st) {
+    const int ofs = min(i, ns - 1) * n_splits * kSkKS;
+    uint16_t* dst = lds + st * STAGE_ELEMS + wave_s * 512;  // one wave-load = 4 rows = 1 KB = 512 elements
 #pragma unroll
-  for (int t = 0; t < MT; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-  u32x4 xr[XCH];
-  bf16x8 wcur[kSkSteps], wnext[kSkSteps];
-  auto gload_x = [&]() {
-#pragma unroll
-    for (int i = 0; i < XCH; ++i) xr[i] = ld16(Xp + xoff[i]);
-    Xp += kSkKS;
-  };
-  auto gload_w = [&](bf16x8* dst) {
-#pragma unroll
-    for (int s = 0; s < kSkSteps; ++s) dst[s] = *reinterpret_cast<const bf16x8*>(Wp + s * 32);
-    Wp += kSkKS;
-  };
-  auto sstore = [&](int buf) {
-    uint16_t* xb = lds + buf * MP * kSkXStride;
-#pragma unroll
-    for (int i = 0; i < XCH; ++i) st16(xb + xlds[i], xr[i]);
+    for (int j = 0; j < G; ++j)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ofs),
+                                       (__attribute__((address_space(3))) void*)(dst + j * kSkWaves * 512), 16,
+                                       0, 0);
   };
 
-  if (ns > 0) {
-    gload_x();
-    gload_w(wcur);
-    sstore(0);
-  }
-  __syncthreads();
+  floatx4 acc[NTW][MT];
+#pragma unroll
+  for (int a = 0; a < NTW; ++a)
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[a][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // fragment read offsets of this wave's two k-steps: lane (row = lane%16, kq = lane/16) reads
+  // chunk 4*step + kq of its row
+  int fo[2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+    fo[s] = (lane & 15) * kSkKS + (((4 * (2 * kh + s) + (lane >> 4)) ^ (lane & 15)) * 8);
+  const int wfrag0 = (MP + ng * NTW * 16) * kSkKS;
+
+#pragma unroll
+  for (int d = 0; d < D; ++d) request(d, d);
+
+  int st = 0;      // stage of slab i
+  int st_req = D;  // stage slab i+D goes to (= the stage slab i-1 used)
   for (int i = 0; i < ns; ++i) {
-    const int buf = i & 1;
-    if (i + 1 < ns) {
-      gload_x();
-      gload_w(wnext);
-    }
-    const uint16_t* xb = lds + buf * MP * kSkXStride + (lane & 15) * kSkXStride + (lane >> 4) * 8;
+    sk_wait_vmcnt<(D - 1) * G>();  // this wave's part of slab i has landed
+    __syncthreads();               // slab i visible to all waves; everyone is done with slab i-1
+    request(i + D, st_req);
+    const uint16_t* sb = lds + st * STAGE_ELEMS;
 #pragma unroll
-    for (int s = 0; s < kSkSteps; ++s) {
+    for (int s = 0; s < 2; ++s) {
+      u32x4 xf[MT];
 #pragma unroll
-      for (int t = 0; t < MT; ++t) {
-        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xb + t * 16 * kSkXStride + s * 32);
-        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wcur[s], xf, acc[t], 0, 0, 0);
+      for (int t = 0; t < MT; ++t) xf[t] = *reinterpret_cast<const u32x4*>(sb + t * 16 * kSkKS + fo[s]);
+#pragma unroll
+      for (int a = 0; a < NTW; ++a) {
+        const u32x4 wf = *reinterpret_cast<const u32x4*>(sb + wfrag0 + a * 16 * kSkKS + fo[s]);
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+          acc[a][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf),
+                                                              __builtin_bit_cast(bf16x8, xf[t]), acc[a][t], 0, 0, 0);
       }
     }
-    if (i + 1 < ns) {
-      sstore(buf ^ 1);
+    st_req = st;
+    st = (st + 1 == S) ? 0 : st + 1;
+  }
+  sk_wait_vmcnt<0>();  // no global->LDS write of this workgroup may still be in flight ...
+  __syncthreads();     // ... and nobody reads the stages any more: reuse them to add the two k-halves
+  {
+    floatx4* red = reinterpret_cast<floatx4*>(lds);  // [4 column groups][NTW][MT][64 lanes]
+    if (kh == 1) {
 #pragma unroll
-      for (int s = 0; s < kSkSteps; ++s) wcur[s] = wnext[s];
+      for (int a = 0; a < NTW; ++a)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) red[((ng * NTW + a) * MT + t) * 64 + lane] = acc[a][t];
     }
     __syncthreads();
+    if (kh == 1) return;
+#pragma unroll
+    for (int a = 0; a < NTW; ++a)
+#pragma unroll
+      for (int t = 0; t < MT; ++t) acc[a][t] += red[((ng * NTW + a) * MT + t) * 64 + lane];
   }
 
-  // acc[t][r]: row m = 16t + lane%16, column n = n0 + 16*wave + 4*(lane/16) + r
-  const int n = n0 + wave * 16 + (lane >> 4) * 4;
-  if (n >= p.N) return;
+  // acc[a][t][r]: row m = 16t + lane%16, column n = n0 + 16*(ng*NTW + a) + 4*(lane/16) + r
 #pragma unroll
-  for (int t = 0; t < MT; ++t) {
-    const int m = t * 16 + (lane & 15);
-    if (m >= p.M) continue;
-    if (gridDim.y > 1) {
-      *reinterpret_cast<floatx4*>(p.partial + ((size_t)split * p.M + m) * p.N + n) = acc[t];
-      continue;
+  for (int a = 0; a < NTW; ++a) {
+    const int n = n0 + (ng * NTW + a) * 16 + (lane >> 4) * 4;
+    if (n >= p.N) continue;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      const int m = t * 16 + (lane & 15);
+      if (m >= p.M) continue;
+      if (n_splits > 1) {
+        *reinterpret_cast<floatx4*>(p.partial + ((size_t)split * p.M + m) * p.N + n) = acc[a][t];
+        continue;
+      }
+      float v0 = acc[a][t][0], v1 = acc[a][t][1], v2 = acc[a][t][2], v3 = acc[a][t][3];
+      if (p.bias) {
+        const u32x2 bb = *reinterpret_cast<const u32x2*>(p.bias + n);
+        v0 += bf16_lo(bb[0]); v1 += bf16_hi(bb[0]);
+        v2 += bf16_lo(bb[1]); v3 += bf16_hi(bb[1]);
+      }
+      if (p.relu) {
+        v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f);
+        v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
+      }
+      if (p.residual) {
+        const u32x2 rr = *reinterpret_cast<const u32x2*>(p.residual + (size_t)m * p.N + n);
+        v0 += bf16_lo(rr[0]); v1 += bf16_hi(rr[0]);
+        v2 += bf16_lo(rr[1]); v3 += bf16_hi(rr[1]);
+      }
+      const int seg = (n >= p.seg_cols) + (n >= 2 * p.seg_cols);
+      u32x2 ov;
+      ov[0] = pack_bf16(v0, v1);
+      ov[1] = pack_bf16(v2, v3);
+      *reinterpret_cast<u32x2*>(p.out[seg] + (size_t)m * p.seg_cols + (n - seg * p.seg_cols)) = ov;
     }
-    float v0 = acc[t][0], v1 = acc[t][1], v2 = acc[t][2], v3 = acc[t][3];
-    if (p.bias) {
-      const u32x2 bb = *reinterpret_cast<const u32x2*>(p.bias + n);
-      v0 += bf16_lo(bb[0]); v1 += bf16_hi(bb[0]);
-      v2 += bf16_lo(bb[1]); v3 += bf16_hi(bb[1]);
-    }
-    if (p.relu) {
-      v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f);
-      v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
-    }
-    if (p.residual) {
-      const u32x2 rr = *reinterpret_cast<const u32x2*>(p.residual + (size_t)m * p.N + n);
-      v0 += bf16_lo(rr[0]); v1 += bf16_hi(rr[0]);
-      v2 += bf16_lo(rr[1]); v3 += bf16_hi(rr[1]);
-    }
-    const int seg = n / p.seg_cols;
-    const int col = n - seg * p.seg_cols;
-    u32x2 ov;
-    ov[0] = pack_bf16(v0, v1);
-    ov[1] = pack_bf16(v2, v3);
-    *reinterpret_cast<u32x2*>(p.out[seg] + (size_t)m * p.seg_cols + col) = ov;
   }
 }
 
@@ -189,36 +234,69 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkinnyParams p
       v[2 * j + 1] += bf16_hi(rr[j]);
     }
   }
-  const int seg = n / p.seg_cols;
-  const int col = n - seg * p.seg_cols;
+  const int seg = (n >= p.seg_cols) + (n >= 2 * p.seg_cols);
   u32x4 ov;
 #pragma unroll
   for (int j = 0; j < 4; ++j) ov[j] = pack_bf16(v[2 * j], v[2 * j + 1]);
-  st16(p.out[seg] + (size_t)m * p.seg_cols + col, ov);
+  st16(p.out[seg] + (size_t)m * p.seg_cols + (n - seg * p.seg_cols), ov);
 }
 
-// Split the K axis until about two workgroups per CU exist, keeping >= 4 slabs per split.
-static int skinny_splits(int N, int K) {
-  const int wgs = (N + kSkBN - 1) / kSkBN;
+int g_skinny_force_ntw = 0;  // development switches (timing harness only): 0 = byte model
+int g_skinny_force_splits = 0;
+
+struct SkinnyPlan {
+  int ntw;     // column tiles per wave: BN = 64 * ntw
+  int splits;  // K splits over workgroups
+};
+
+// Measured on MI355X: a CU sustains about one workgroup's worth of streaming whatever the LDS would
+// allow, and a second round of workgroups costs a full round.  So a plan must fit one round
+// (<= 256 workgroups) and should fill it; among such plans take the fewest bytes through the CUs' L1:
+//   weights + (N/BN) * X (each column block re-reads the activations) + partial sums written and
+//   read back.
+static SkinnyPlan skinny_plan(int M, int N, int K) {
   const int slabs = K / kSkKS;
-  int splits = (2 * 256 + wgs - 1) / wgs;
-  const int max_splits = slabs / 4 > 0 ? slabs / 4 : 1;
-  if (splits > max_splits) splits = max_splits;
-  if (splits < 1) splits = 1;
-  const int per = (slabs + splits - 1) / splits;
-  return (slabs + per - 1) / per;  // drop empty splits
+  const int mp = M <= 64 ? 64 : (M <= 128 ? 128 : 256);
+  SkinnyPlan best{1, 1};
+  double best_cost = 1e300;
+  for (int ntw = 1; ntw <= 4; ntw *= 2) {
+    if (g_skinny_force_ntw > 0 && ntw != g_skinny_force_ntw) continue;
+    const int bn = 64 * ntw;
+    if (mp == 256 && ntw > 1) continue;  // (256 + 128) * 256 B * 2 stages does not fit the LDS
+    if (mp == 128 && ntw > 2) continue;
+    const int wgs_n = (N + bn - 1) / bn;
+    for (int splits = 1; splits <= slabs && splits <= 64; ++splits) {
+      if (g_skinny_force_splits > 0 && splits != g_skinny_force_splits) continue;
+      const double wgs = (double)wgs_n * splits;
+      const bool forced = g_skinny_force_splits > 0;
+      if (wgs > 256.0 && splits > 1 && !forced) break;        // never split into a second round
+      const double rounds = wgs <= 256.0 ? 1.0 : wgs / 256.0;  // unsplit but larger than the chip
+      const double fill = wgs >= 256.0 ? 1.0 : 256.0 / wgs;    // idle CUs stretch the time
+      const double bytes = 2.0 * N * K + 2.0 * wgs_n * (double)mp * K +
+                           (splits > 1 ? 2.0 * 4.0 * splits * (double)M * N : 0.0);
+      const double cost = bytes * fill * rounds;
+      if (cost < best_cost) {
+        best_cost = cost;
+        best = SkinnyPlan{ntw, splits};
+      }
+    }
+  }
+  return best;
 }
 
 size_t skinny_workspace_bytes(int M, int N, int K) {
-  if (K % kSkKS != 0) return 0;
-  const int splits = skinny_splits(N, K);
-  return splits > 1 ? (size_t)splits * M * N * sizeof(float) : 0;
+  if (K % kSkKS != 0 || M > 256) return 0;
+  const SkinnyPlan pl = skinny_plan(M, N, K);
+  return pl.splits > 1 ? (size_t)pl.splits * M * N * sizeof(float) : 0;
 }
 
-template <int MT>
-static hipError_t launch_skinny_mt(const SkinnyParams& p, int splits, hipStream_t stream) {
-  constexpr size_t lds_bytes = 2ull * MT * 16 * kSkXStride * sizeof(uint16_t);
-  auto kern = skinny_gemm_kernel<MT>;
+template <int MT, int NTW, int S>
+static hipError_t launch_skinny_cfg(const SkinnyParams& p, int splits, hipStream_t stream) {
+  constexpr int BN = 64 * NTW;
+  constexpr size_t lds_bytes = (size_t)S * (MT * 16 + BN) * kSkKS * sizeof(uint16_t);
+  static_assert(lds_bytes <= 160 * 1024, "LDS");
+  static_assert((size_t)4 * NTW * MT * 64 * 16 <= lds_bytes, "k-half reduction fits the stages");
+  auto kern = skinny_gemm_kernel<MT, NTW, S>;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -226,7 +304,7 @@ static hipError_t launch_skinny_mt(const SkinnyParams& p, int splits, hipStream_
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3((p.N + kSkBN - 1) / kSkBN, splits), dim3(kSkThreads), lds_bytes, stream, p);
+  hipLaunchKernelGGL(kern, dim3((p.N + BN - 1) / BN, splits), dim3(kSkThreads), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
@@ -235,6 +313,7 @@ hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K,
   if (M <= 0 || N <= 0) return hipSuccess;
   if (M > 256 || K % kSkKS != 0 || N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0)
     return hipErrorInvalidValue;
+  if (ep.residual && ep.seg_cols != N) return hipErrorInvalidValue;
   SkinnyParams p;
   p.X = (const uint16_t*)X;
   p.W = (const uint16_t*)W;
@@ -244,23 +323,26 @@ hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K,
   p.seg_cols = ep.seg_cols;
   p.M = M; p.N = N; p.K = K;
   p.relu = ep.relu;
-  const int splits = skinny_splits(N, K);
-  const int slabs = K / kSkKS;
-  p.slabs_per_split = (slabs + splits - 1) / splits;
+  const SkinnyPlan pl = skinny_plan(M, N, K);
   p.partial = (float*)workspace;
-  if (splits > 1 && workspace == nullptr) return hipErrorInvalidValue;
+  if (pl.splits > 1 && workspace == nullptr) return hipErrorInvalidValue;
   hipError_t e;
-  const int mt = (M + 15) / 16;
-  if (mt <= 1) e = launch_skinny_mt<1>(p, splits, stream);
-  else if (mt <= 2) e = launch_skinny_mt<2>(p, splits, stream);
-  else if (mt <= 4) e = launch_skinny_mt<4>(p, splits, stream);
-  else if (mt <= 8) e = launch_skinny_mt<8>(p, splits, stream);
-  else e = launch_skinny_mt<16>(p, splits, stream);
+  // fewer than 64 rows run as 64 (clamped duplicates; the matrix cores are idle anyway)
+  if (M <= 64) {
+    if (pl.ntw == 4) e = launch_skinny_cfg<4, 4, 2>(p, pl.splits, stream);       // 160 KB
+    else if (pl.ntw == 2) e = launch_skinny_cfg<4, 2, 3>(p, pl.splits, stream);  // 144 KB
+    else e = launch_skinny_cfg<4, 1, 2>(p, pl.splits, stream);                   //  64 KB
+  } else if (M <= 128) {
+    if (pl.ntw == 2) e = launch_skinny_cfg<8, 2, 2>(p, pl.splits, stream);       // 128 KB
+    else e = launch_skinny_cfg<8, 1, 3>(p, pl.splits, stream);                   // 144 KB
+  } else {
+    e = launch_skinny_cfg<16, 1, 2>(p, pl.splits, stream);                       // 160 KB
+  }
   if (e != hipSuccess) return e;
-  if (splits > 1) {
+  if (pl.splits > 1) {
     const long items = (long)M * (N / 8);
     hipLaunchKernelGGL(skinny_reduce_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, p,
-                       splits);
+                       pl.splits);
     e = hipGetLastError();
   }
   return e;
