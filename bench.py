@@ -32,6 +32,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--small", action="store_true", help="tiny config (debug only; not a valid bench line)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run a plain 1 GiB device copy (known traffic) for calibrating rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -109,6 +112,15 @@ def main():
             ctx.ds_decode_step(lw, x_dec[j], ctx_all[j], bt_dev, B_dec, max_blocks, ctx0 + j + 1, k_cache, v_cache,
                                nblk, y_dec, ws_dec)
 
+    if args.copy_calibration:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        a.fill_(1)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
     # ---------------- warm-up, then the timed region ----------------
     for _ in range(args.warmup):
         one_step()
@@ -159,6 +171,16 @@ def main():
         "decode_attn": ("hbm", sum(cost.decode_attention_bytes(kl, h) for kl in kv_lens_steps), cost.PEAK_HBM_BYTES),
         "kv_append": ("hbm", steps_dec * cost.kv_append_bytes(B_dec, h), cost.PEAK_HBM_BYTES),
     }
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (separate runs of this same
+    # command, scaled by a known-size copy); the summary and its commands are kept under profiles/.
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "bench_opt13b_1layer_hbm_traffic.json")
+    if not args.small and os.path.exists(tpath):
+        with open(tpath) as f:
+            per = json.load(f)["per_launch"]
+        traffic = {k: v["hbm_read_bytes"] + v["hbm_write_bytes"] for k, v in per.items()}
+        if "skinny_reduce" in per:   # the class timed as skinny_gemm includes its split-K reduce launch
+            traffic["skinny_gemm"] += per["skinny_reduce"]["hbm_read_bytes"] + per["skinny_reduce"]["hbm_write_bytes"]
     kernels = {}
     for name, (bound, amount, peak) in work.items():
         ms, cnt = prof[name]
@@ -171,7 +193,8 @@ def main():
         kernels[name] = {"bound": bound, "achieved": round(rate / unit_scale, 2), "peak": peak / unit_scale,
                          "unit": unit, "frac": round(rate / peak, 4), "launches_per_step": int(cnt),
                          "avg_launch_us": round(ms * 1e3 / cnt, 2), "ms_per_step": round(ms, 4),
-                         "traffic": None}
+                         "algorithmic_per_launch": round(amount / cnt),
+                         "traffic": traffic.get(name)}
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     roofline = dict(kernels[dominant])
     roofline["kernel"] = dominant
