@@ -57,7 +57,7 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((VM & 0xf) | (0x7 << 4) | (0xf << 8) | ((VM >> 4) << 14));
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int Q0N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
 __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams p) {
   static_assert(WAVES_M * WAVES_N == 4, "4 waves");
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   constexpr int XL = BM / 32;                             // X loads per wave per stage
   constexpr int WL = BN / 32;                             // W loads per wave per stage
   constexpr int LPS = XL + WL;
-  static_assert(LPS + Q0N < 64 && Q0N <= LPS, "vmcnt range");
+  static_assert(2 * LPS < 64, "vmcnt range");
 
   extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
 
@@ -136,90 +136,84 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   const int xrow0 = (wm * WTM + frag_row) * kBK;
   const int wrow0 = BM * kBK + (wn * WTN + frag_row) * kBK;
 
-  // Fragment registers are double-buffered: while the MFMAs of k-step kk run,
-  // the ds_reads of k-step kk+1 (or of k-step 0 of the next tile) are in flight.
+  // A k-tile (4 MFMA k-steps) is multiplied in two halves of two k-steps each.  Within a half every
+  // accumulator tile gets its two MFMAs back to back (the second one chains on the first one's
+  // result, which the matrix pipe issues without a bubble; a round-robin over 10 accumulators was
+  // measured ~15 % slower with one wave per SIMD).  The fragments of the next half are fetched
+  // while the current half is multiplied, so two fragment sets of 2 x (TN + TM) registers exist.
   // (held as integer vectors: bf16 vectors carried around the loop get re-packed by the compiler)
-  u32x4 wfa[TN], xfa[TM], wfb[TN], xfb[TM];
-  auto load_frags = [&](u32x4* wf, u32x4* xf, const uint16_t* sb, int kk) {
-#pragma unroll
-    for (int a = 0; a < TN; ++a) wf[a] = *reinterpret_cast<const u32x4*>(sb + wrow0 + a * 32 * kBK + koff[kk]);
-#pragma unroll
-    for (int b = 0; b < TM; ++b) xf[b] = *reinterpret_cast<const u32x4*>(sb + xrow0 + b * 32 * kBK + koff[kk]);
+  struct Frags {
+    u32x4 w[2][TN];
+    u32x4 x[2][TM];
+  };
+  Frags fa, fb;
+  constexpr int NR = 2 * (TN + TM);  // fragment reads per half
+  // read number r of the half starting at k-step kk0 of stage buffer sb
+  auto frag_read = [&](Frags& f, const uint16_t* sb, int kk0, int r) {
+    const int s2 = r / (TN + TM), q = r % (TN + TM);
+    if (q < TN) f.w[s2][q] = *reinterpret_cast<const u32x4*>(sb + wrow0 + q * 32 * kBK + koff[kk0 + s2]);
+    else f.x[s2][q - TN] = *reinterpret_cast<const u32x4*>(sb + xrow0 + (q - TN) * 32 * kBK + koff[kk0 + s2]);
   };
 
-  // Pipeline over 3 LDS buffers with ONE barrier per k-tile and two k-tiles of flight time per load:
-  //   iteration kt:  k-steps 0..2 of tile kt (fragments of step kk+1 fetched during step kk)
-  //                  wait until this wave's part of tile kt+1 has landed (tile kt+2 may still fly)
-  //                  barrier: tile kt+1 is visible to all, and nobody reads buffer kt%3 any more
-  //                           (the step-3 fragments of tile kt are already in registers)
-  //                  issue tile kt+3 into buffer kt%3
-  //                  k-step 3 of tile kt, fetching the step-0 fragments of tile kt+1
-  static_assert(STAGES == 3, "the schedule below is written for 3 buffers");
-  issue(0, 0);
-  issue(1, 1);
-#pragma unroll
-  for (int j = 0; j < Q0N; ++j) issue_one(2, 2, j);   // quarter 0 of tile 2; the loop issues the rest
-  wait_vmcnt<LPS + Q0N>();
-  __syncthreads();
-  load_frags(wfa, xfa, lds, 0);
-
-  // One phase = the MFMAs of one k-step.  After MFMA i the code issues one fragment read of the
-  // next k-step (while there are any) and a share of the global->LDS loads; a scheduling fence
-  // after every such group keeps that interleaving, so the memory instructions issue in the shadow
-  // of the 32-cycle MFMAs instead of in bursts.  The LPS loads of a tile are spread over four
-  // phases (quarter Q = loads [Q*LPS/4, (Q+1)*LPS/4)): the four waves share one address unit, and
-  // a burst of all their loads in one phase would stall the matrix pipe behind the load queue.
-  auto phase = [&](auto quarter, const u32x4* wc, const u32x4* xc, u32x4* wn_, u32x4* xn_,
-                   const uint16_t* sb_next, int kk_next, int ld_stage, int ld_tile) {
+  // One half: after each accumulator's MFMA pair the code issues a share of the next half's fragment
+  // reads and (in the second half of a tile) of the global->LDS loads of tile kt+3; a scheduling
+  // fence after every group keeps that interleaving, so memory instructions issue in the shadow of
+  // the MFMAs instead of in bursts.
+  // `mem(j)` is called for j = 0 .. JN-1, spread evenly over the MFMA pairs: it issues the j-th
+  // direct-to-LDS load of this half.
+  auto half = [&](auto jn, const Frags& fc, Frags& fn, const uint16_t* sb_next, int kk_next, auto&& mem) {
     constexpr int NM = TM * TN;
-    constexpr int Q = decltype(quarter)::value;
-    // Q0N = loads issued in quarter 0 (right after the barrier); the rest is split over quarters 1..3
-    constexpr int JLO = Q == 0 ? 0 : Q0N + (Q - 1) * (LPS - Q0N) / 3;
-    constexpr int JHI = Q == 0 ? Q0N : Q0N + Q * (LPS - Q0N) / 3;
-    constexpr int JN = JHI - JLO;
+    constexpr int JN = decltype(jn)::value;
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
       const int a = i / TM, b = i % TM;
-      acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wc[a]),
-                                                          __builtin_bit_cast(bf16x8, xc[b]), acc[a][b], 0, 0, 0);
-      if (i < TN)
-        wn_[i] = *reinterpret_cast<const u32x4*>(sb_next + wrow0 + i * 32 * kBK + koff[kk_next]);
-      else if (i < TN + TM)
-        xn_[i - TN] = *reinterpret_cast<const u32x4*>(sb_next + xrow0 + (i - TN) * 32 * kBK + koff[kk_next]);
+      acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fc.w[0][a]),
+                                                          __builtin_bit_cast(bf16x8, fc.x[0][b]), acc[a][b], 0, 0, 0);
+      acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fc.w[1][a]),
+                                                          __builtin_bit_cast(bf16x8, fc.x[1][b]), acc[a][b], 0, 0, 0);
 #pragma unroll
-      for (int j = i * JN / NM; j < (i + 1) * JN / NM; ++j) issue_one(ld_stage, ld_tile, JLO + j);
+      for (int r = i * NR / NM; r < (i + 1) * NR / NM; ++r) frag_read(fn, sb_next, kk_next, r);
+#pragma unroll
+      for (int j = i * JN / NM; j < (i + 1) * JN / NM; ++j) mem(j);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  using Q0 = std::integral_constant<int, 0>;
-  using Q1 = std::integral_constant<int, 1>;
-  using Q2 = std::integral_constant<int, 2>;
-  using Q3 = std::integral_constant<int, 3>;
+  using none = std::integral_constant<int, 0>;
+  using all_loads = std::integral_constant<int, LPS>;
+  auto no_mem = [](int) {};
 
-  // Schedule (3 LDS buffers, ONE barrier per k-tile, about two k-tiles of flight time per load):
-  //   iteration kt:  k-steps 0..2 of tile kt, carrying quarters 1..3 of the loads of tile kt+2
-  //                  wait until this wave's part of tile kt+1 has landed (tile kt+2 may still fly)
-  //                  barrier: tile kt+1 is visible to all, and nobody reads buffer kt%3 any more
-  //                           (the step-3 fragments of tile kt are already in registers)
-  //                  k-step 3 of tile kt, carrying quarter 0 of the loads of tile kt+3 (into buffer
-  //                  kt%3) and fetching the step-0 fragments of tile kt+1
-  int stage = 0;                       // buffer of tile kt
-  int stage2 = 2;                      // buffer of tile kt+2
-  for (int kt = 0; kt < KT; ++kt) {
-    const uint16_t* sb = lds + stage * STAGE_ELEMS;
-    int nstage = stage + 1;
-    if (nstage == STAGES) nstage = 0;
-    const uint16_t* sbn = lds + nstage * STAGE_ELEMS;
-    __builtin_amdgcn_sched_barrier(0);
-    phase(Q1{}, wfa, xfa, wfb, xfb, sb, 1, stage2, kt + 2);
-    phase(Q2{}, wfb, xfb, wfa, xfa, sb, 2, stage2, kt + 2);
-    phase(Q3{}, wfa, xfa, wfb, xfb, sb, 3, stage2, kt + 2);
-    wait_vmcnt<LPS>();
+  {
+    // Direct-to-LDS schedule (3 LDS buffers, ONE barrier per k-tile, two k-tiles of flight time):
+    //   iteration kt:  first half of tile kt (fetching the fragments of its second half)
+    //                  wait until this wave's part of tile kt+1 has landed (tile kt+2 may still fly)
+    //                  barrier: tile kt+1 is visible to all, and nobody reads buffer kt%3 any more
+    //                           (the second half's fragments are already in registers)
+    //                  second half of tile kt, issuing the loads of tile kt+3 into buffer kt%3 and
+    //                  fetching the first-half fragments of tile kt+1
+    static_assert(STAGES == 3, "the schedule is written for 3 buffers");
+    issue(0, 0);
+    issue(1, 1);
+    issue(2, 2);
+    wait_vmcnt<2 * LPS>();
     __syncthreads();
-    // (past the last tile the fragment fetch reads a stale buffer; the values are never used)
-    phase(Q0{}, wfb, xfb, wfa, xfa, sbn, 0, stage, kt + 3);
-    stage2 = stage;
-    stage = nstage;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) frag_read(fa, lds, 0, r);
+
+    int stage = 0;  // buffer of tile kt
+    for (int kt = 0; kt < KT; ++kt) {
+      const uint16_t* sb = lds + stage * STAGE_ELEMS;
+      int nstage = stage + 1;
+      if (nstage == STAGES) nstage = 0;
+      const uint16_t* sbn = lds + nstage * STAGE_ELEMS;
+      __builtin_amdgcn_sched_barrier(0);
+      half(none{}, fa, fb, sb, 2, no_mem);
+      wait_vmcnt<LPS>();
+      __syncthreads();
+      // (past the last tile the fragment fetch reads a stale buffer; the values are never used)
+      half(all_loads{}, fb, fa, sbn, 0, [&](int j) { issue_one(stage, kt + 3, j); });
+      stage = nstage;
+    }
+    wait_vmcnt<0>();  // the clamped re-loads of the loop tail must not land in the epilogue's staging area
   }
 
   // ---- epilogue through LDS: every lane ends up with 8 consecutive columns of one row, so bias,
@@ -231,10 +225,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   constexpr int GA_FIT = (LDS_FLOATS / (4 * WTM) - 4) / 32;
   constexpr int GA = GA_FIT < TN ? GA_FIT : TN;
   static_assert(GA >= 1, "no room to stage the epilogue");
-  constexpr int RS = GA * 32 + 4;  // staging row stride in floats
-  wait_vmcnt<0>();                 // the clamped re-loads of the loop tail must not land in the staging area
+  constexpr int RSTR = GA * 32 + 4;  // staging row stride in floats
   __syncthreads();                 // every wave has finished reading the k-loop buffers
-  float* stg = reinterpret_cast<float*>(lds) + wave * (WTM * RS);
+  float* stg = reinterpret_cast<float*>(lds) + wave * (WTM * RSTR);
   const int row_base = m0 + wm * WTM;
   const int col_base = n0 + wn * WTN;
 #pragma unroll
@@ -253,7 +246,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
           floatx4 v;
           v[0] = acc[a0 + a][b][4 * g + 0]; v[1] = acc[a0 + a][b][4 * g + 1];
           v[2] = acc[a0 + a][b][4 * g + 2]; v[3] = acc[a0 + a][b][4 * g + 3];
-          *reinterpret_cast<floatx4*>(stg + (b * 32 + (lane & 31)) * RS + a * 32 + g * 8 + (lane >> 5) * 4) = v;
+          *reinterpret_cast<floatx4*>(stg + (b * 32 + (lane & 31)) * RSTR + a * 32 + g * 8 + (lane >> 5) * 4) = v;
         }
     }
     // 2. read back row-contiguous: chunk = 8 columns; cpr chunks per row
@@ -279,8 +272,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
       const int idx = it * 64 + lane;
       const int r = idx / cpr, ch = idx - r * cpr;
       const int row = row_base + r, n = col_base + a0 * 32 + ch * 8;
-      const floatx4 lo = *reinterpret_cast<const floatx4*>(stg + r * RS + ch * 8);
-      const floatx4 hi = *reinterpret_cast<const floatx4*>(stg + r * RS + ch * 8 + 4);
+      const floatx4 lo = *reinterpret_cast<const floatx4*>(stg + r * RSTR + ch * 8);
+      const floatx4 hi = *reinterpret_cast<const floatx4*>(stg + r * RSTR + ch * 8 + 4);
       float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       u32x4 o;
 #pragma unroll
@@ -303,13 +296,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int Q0N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
 static hipError_t launch_dl(GemmParams p, hipStream_t stream) {
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N + BN - 1) / BN;
   constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * kBK * sizeof(uint16_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS");
-  auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, Q0N>;
+  auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, STAGES>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -355,8 +348,8 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
     variant = small < big ? 2 : 1;
   }
   switch (variant) {
-    case 2: return launch_dl<128, 128, 2, 2, 3, 8>(p, stream);
-    default: return launch_dl<256, 160, 4, 1, 3, 13>(p, stream);
+    case 2: return launch_dl<128, 128, 2, 2, 3>(p, stream);
+    default: return launch_dl<256, 160, 4, 1, 3>(p, stream);
   }
 }
 
