@@ -98,12 +98,14 @@ struct Carver {
 bool use_skinny(int rows, int in_f) { return rows <= kSkinnyMaxRows && in_f % 128 == 0; }
 
 ds_status linear(ds_ctx* ctx, const void* x, const void* w, int rows, int in_f, int out_f,
-                 const ds::Epilogue& ep, void* skinny_ws, hipStream_t stream) {
+                 const ds::Epilogue& ep, void* skinny_ws, hipStream_t stream,
+                 const ds::SkinnyFused* fused = nullptr, bool* fused_done = nullptr) {
+  if (fused_done) *fused_done = false;
   if (use_skinny(rows, in_f)) {
     hipError_t e;
     {
       Timed t(ctx, stream, DS_K_SKINNY_GEMM);
-      e = ds::launch_skinny_gemm(x, w, rows, out_f, in_f, ep, skinny_ws, stream);
+      e = ds::launch_skinny_gemm(x, w, rows, out_f, in_f, ep, skinny_ws, stream, fused, fused_done);
     }
     if (e != hipSuccess) return fail(ctx, DS_ERR_HIP, "skinny gemm failed: %s", hipGetErrorString(e));
     return DS_OK;
@@ -390,28 +392,41 @@ ds_status ds_decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, 
   void* sk = ws.take(0);
 
   DS_LAUNCH(ctx, s, DS_K_LAYERNORM, ds::launch_layernorm(x, w->ln1_g, w->ln1_b, a, B, h, c.ln_eps, s));
+  const uint16_t* qkv16 = static_cast<const uint16_t*>(qkv);
   {
+    // [q | k | v] = a W_qkv^T + b_qkv; the split-K reduction writes k, v straight into the cache
     ds::Epilogue ep;
     ep.bias = w->b_qkv;
     ep.out[0] = qkv; ep.seg_cols = 3 * h;
-    st = linear(ctx, a, w->w_qkv, B, h, 3 * h, ep, sk, s);
+    ds::SkinnyFused fu;
+    fu.kind = ds::SkinnyFused::kKvAppend;
+    fu.ctx_lens = ctx_lens; fu.block_tables = block_tables; fu.max_blocks = max_blocks_per_seq;
+    fu.k_cache = k_cache; fu.v_cache = v_cache; fu.n_heads = c.n_heads; fu.head_dim = c.head_dim;
+    bool appended = false;
+    st = linear(ctx, a, w->w_qkv, B, h, 3 * h, ep, sk, s, &fu, &appended);
     if (st != DS_OK) return st;
+    if (!appended)
+      DS_LAUNCH(ctx, s, DS_K_KV_APPEND,
+                ds::launch_kv_append(qkv16 + h, qkv16 + 2 * h, 3 * h, ctx_lens, block_tables, B, max_blocks_per_seq,
+                                     k_cache, v_cache, c.n_heads, c.head_dim, s));
   }
-  const uint16_t* qkv16 = static_cast<const uint16_t*>(qkv);
-  DS_LAUNCH(ctx, s, DS_K_KV_APPEND,
-            ds::launch_kv_append(qkv16 + h, qkv16 + 2 * h, 3 * h, ctx_lens, block_tables, B, max_blocks_per_seq,
-                                 k_cache, v_cache, c.n_heads, c.head_dim, s));
   DS_LAUNCH(ctx, s, DS_K_DECODE_ATTN,
             ds::launch_decode_attention(qkv, 3 * h, ctx_lens, 1, block_tables, B, max_blocks_per_seq, max_ctx,
                                         k_cache, v_cache, c.n_heads, c.head_dim, o, att, s));
   {
+    // x1 = x + o W_o^T + b_o, and f = LN2(x1) in the same reduction pass
     ds::Epilogue ep;
     ep.bias = w->b_o; ep.residual = x;
     ep.out[0] = x1; ep.seg_cols = h;
-    st = linear(ctx, o, w->w_o, B, h, h, ep, sk, s);
+    ds::SkinnyFused fu;
+    fu.kind = ds::SkinnyFused::kLayerNorm;
+    fu.ln_gamma = w->ln2_g; fu.ln_beta = w->ln2_b; fu.ln_eps = c.ln_eps; fu.ln_out = a;
+    bool normed = false;
+    st = linear(ctx, o, w->w_o, B, h, h, ep, sk, s, &fu, &normed);
     if (st != DS_OK) return st;
+    if (!normed)
+      DS_LAUNCH(ctx, s, DS_K_LAYERNORM, ds::launch_layernorm(x1, w->ln2_g, w->ln2_b, a, B, h, c.ln_eps, s));
   }
-  DS_LAUNCH(ctx, s, DS_K_LAYERNORM, ds::launch_layernorm(x1, w->ln2_g, w->ln2_b, a, B, h, c.ln_eps, s));
   {
     ds::Epilogue ep;
     ep.bias = w->b_fc1; ep.relu = 1;

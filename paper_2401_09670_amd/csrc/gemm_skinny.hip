@@ -241,6 +241,159 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkinnyParams p
   st16(p.out[seg] + (size_t)m * p.seg_cols + (n - seg * p.seg_cols), ov);
 }
 
+// The same reduction, one workgroup per output row, followed by LayerNorm of that row: writes
+// out[0][m,:] = act(sum + bias) + residual (bf16) and ln_out[m,:] = LN(out[m,:]) (statistics in
+// fp32 over the bf16-rounded row, exactly what the stand-alone LayerNorm kernel would see).
+constexpr int kRedLnMaxChunks = 8;  // 8 chunks x 8 columns x 256 threads = 16384 columns
+__global__ __launch_bounds__(256) void skinny_reduce_ln_kernel(const SkinnyParams p, int n_splits,
+                                                               const uint16_t* __restrict__ gamma,
+                                                               const uint16_t* __restrict__ beta, float eps,
+                                                               uint16_t* __restrict__ ln_out) {
+  __shared__ float red[4];
+  const int m = blockIdx.x;
+  const int nchunk = p.N >> 3;
+  float vals[kRedLnMaxChunks][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < kRedLnMaxChunks; ++i) {
+    const int c = threadIdx.x + i * 256;
+    if (c < nchunk) {
+      const int n = c * 8;
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = 0.f;
+      for (int s = 0; s < n_splits; ++s) {
+        const float* src = p.partial + ((size_t)s * p.M + m) * p.N + n;
+        const floatx4 a = *reinterpret_cast<const floatx4*>(src);
+        const floatx4 b = *reinterpret_cast<const floatx4*>(src + 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          v[j] += a[j];
+          v[4 + j] += b[j];
+        }
+      }
+      if (p.bias) {
+        const u32x4 bb = ld16(p.bias + n);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          v[2 * j] += bf16_lo(bb[j]);
+          v[2 * j + 1] += bf16_hi(bb[j]);
+        }
+      }
+      if (p.relu) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = fmaxf(v[j], 0.f);
+      }
+      if (p.residual) {
+        const u32x4 rr = ld16(p.residual + (size_t)m * p.N + n);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          v[2 * j] += bf16_lo(rr[j]);
+          v[2 * j + 1] += bf16_hi(rr[j]);
+        }
+      }
+      u32x4 ov;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        ov[j] = pack_bf16(v[2 * j], v[2 * j + 1]);
+        vals[i][2 * j] = bf16_lo(ov[j]);
+        vals[i][2 * j + 1] = bf16_hi(ov[j]);
+        sum += vals[i][2 * j] + vals[i][2 * j + 1];
+      }
+      st16(p.out[0] + (size_t)m * p.N + n, ov);
+    }
+  }
+  auto block_sum = [&](float v) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+  };
+  const float mean = block_sum(sum) / (float)p.N;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < kRedLnMaxChunks; ++i) {
+    const int c = threadIdx.x + i * 256;
+    if (c < nchunk) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float d = vals[i][j] - mean;
+        sq += d * d;
+      }
+    }
+  }
+  const float rstd = rsqrtf(block_sum(sq) / (float)p.N + eps);
+#pragma unroll
+  for (int i = 0; i < kRedLnMaxChunks; ++i) {
+    const int c = threadIdx.x + i * 256;
+    if (c < nchunk) {
+      const u32x4 g = ld16(gamma + c * 8);
+      const u32x4 b = ld16(beta + c * 8);
+      u32x4 o;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float lo = (vals[i][2 * j] - mean) * rstd * bf16_lo(g[j]) + bf16_lo(b[j]);
+        const float hi = (vals[i][2 * j + 1] - mean) * rstd * bf16_hi(g[j]) + bf16_hi(b[j]);
+        o[j] = pack_bf16(lo, hi);
+      }
+      st16(ln_out + (size_t)m * p.N + c * 8, o);
+    }
+  }
+}
+
+// The same reduction for the decode QKV projection (N = 3h, one output buffer with row stride 3h):
+// the Q third is written to out[0]; the K and V thirds are this step's new cache rows and go to
+// slot ctx_lens[m] of the paged cache [num_blocks, heads, 16, head_dim].
+__global__ __launch_bounds__(256) void skinny_reduce_kv_kernel(const SkinnyParams p, int n_splits,
+                                                               const int32_t* __restrict__ ctx_lens,
+                                                               const int32_t* __restrict__ block_tables,
+                                                               int max_blocks, uint16_t* __restrict__ k_cache,
+                                                               uint16_t* __restrict__ v_cache, int n_heads,
+                                                               int head_dim) {
+  const int chunks_per_row = p.N >> 3;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)p.M * chunks_per_row) return;
+  const int m = (int)(idx / chunks_per_row);
+  const int n = (int)(idx % chunks_per_row) * 8;
+  float v[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float* src = p.partial + ((size_t)s * p.M + m) * p.N + n;
+    const floatx4 a = *reinterpret_cast<const floatx4*>(src);
+    const floatx4 b = *reinterpret_cast<const floatx4*>(src + 4);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      v[j] += a[j];
+      v[4 + j] += b[j];
+    }
+  }
+  if (p.bias) {
+    const u32x4 bb = ld16(p.bias + n);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      v[2 * j] += bf16_lo(bb[j]);
+      v[2 * j + 1] += bf16_hi(bb[j]);
+    }
+  }
+  u32x4 ov;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) ov[j] = pack_bf16(v[2 * j], v[2 * j + 1]);
+  const int h = n_heads * head_dim;
+  if (n < h) {
+    st16(p.out[0] + (size_t)m * p.N + n, ov);
+    return;
+  }
+  const int which = n >= 2 * h;
+  const int col = n - h * (1 + which);
+  const int head = col / head_dim, d = col - head * head_dim;
+  const int pos = ctx_lens[m];
+  const int blk = block_tables[(size_t)m * max_blocks + pos / 16];
+  uint16_t* dst = (which ? v_cache : k_cache) + (((size_t)blk * n_heads + head) * 16 + (pos % 16)) * head_dim + d;
+  st16(dst, ov);
+}
+
 int g_skinny_force_ntw = 0;  // development switches (timing harness only): 0 = byte model
 int g_skinny_force_splits = 0;
 
@@ -309,7 +462,8 @@ static hipError_t launch_skinny_cfg(const SkinnyParams& p, int splits, hipStream
 }
 
 hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
-                              void* workspace, hipStream_t stream) {
+                              void* workspace, hipStream_t stream, const SkinnyFused* fused, bool* fused_done) {
+  if (fused_done) *fused_done = false;
   if (M <= 0 || N <= 0) return hipSuccess;
   if (M > 256 || K % kSkKS != 0 || N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0)
     return hipErrorInvalidValue;
@@ -341,8 +495,21 @@ hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K,
   if (e != hipSuccess) return e;
   if (pl.splits > 1) {
     const long items = (long)M * (N / 8);
-    hipLaunchKernelGGL(skinny_reduce_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream, p,
-                       pl.splits);
+    const unsigned blocks = (unsigned)((items + 255) / 256);
+    if (fused && fused->kind == SkinnyFused::kLayerNorm && ep.seg_cols == N && N <= 256 * 8 * kRedLnMaxChunks) {
+      hipLaunchKernelGGL(skinny_reduce_ln_kernel, dim3(M), dim3(256), 0, stream, p, pl.splits,
+                         (const uint16_t*)fused->ln_gamma, (const uint16_t*)fused->ln_beta, fused->ln_eps,
+                         (uint16_t*)fused->ln_out);
+      if (fused_done) *fused_done = true;
+    } else if (fused && fused->kind == SkinnyFused::kKvAppend && ep.seg_cols == N && !ep.relu && !ep.residual &&
+               N == 3 * fused->n_heads * fused->head_dim) {
+      hipLaunchKernelGGL(skinny_reduce_kv_kernel, dim3(blocks), dim3(256), 0, stream, p, pl.splits,
+                         fused->ctx_lens, fused->block_tables, fused->max_blocks, (uint16_t*)fused->k_cache,
+                         (uint16_t*)fused->v_cache, fused->n_heads, fused->head_dim);
+      if (fused_done) *fused_done = true;
+    } else {
+      hipLaunchKernelGGL(skinny_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p, pl.splits);
+    }
     e = hipGetLastError();
   }
   return e;

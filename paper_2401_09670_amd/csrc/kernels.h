@@ -27,10 +27,31 @@ struct Epilogue {
 hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
                        hipStream_t stream);
 
+// Work that the decode GEMM's split-K reduction can absorb (saves a launch each):
+//  kLayerNorm: after out = act(..) + residual is written, also write ln_out = LN(out) (row-wise).
+//  kKvAppend : columns [0, h) go to out[0] as usual; columns [h, 2h) / [2h, 3h) are this step's K / V
+//              rows and go straight into the paged cache at position ctx_lens[row].
+struct SkinnyFused {
+  enum Kind { kNone = 0, kLayerNorm = 1, kKvAppend = 2 } kind = kNone;
+  const void* ln_gamma = nullptr;
+  const void* ln_beta = nullptr;
+  float ln_eps = 0.f;
+  void* ln_out = nullptr;
+  const int32_t* ctx_lens = nullptr;
+  const int32_t* block_tables = nullptr;
+  int max_blocks = 0;
+  void* k_cache = nullptr;
+  void* v_cache = nullptr;
+  int n_heads = 0, head_dim = 0;
+};
+
 // Same contraction for M <= 256 (decode): weights are streamed once from HBM.
+// `*fused_done` tells whether the requested fused work was carried out (it needs the split-K
+// reduction pass); if not, the caller launches the separate kernel.
 size_t skinny_workspace_bytes(int M, int N, int K);
 hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
-                              void* workspace, hipStream_t stream);
+                              void* workspace, hipStream_t stream, const SkinnyFused* fused = nullptr,
+                              bool* fused_done = nullptr);
 
 // Causal attention within each packed request; q,k,v,o rows have `n_heads*head_dim` elements.
 hipError_t launch_prefill_attention(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
