@@ -49,3 +49,34 @@ def update_ok(y_gpu: np.ndarray, y_ref: np.ndarray, x_in: np.ndarray) -> bool:
     upd_ref = y_ref - x_in
     bound = 2 * 2.0 ** -9 * np.max(np.abs(y_ref)) + 1e-2 * np.max(np.abs(upd_ref))
     return bool(np.max(np.abs((y_gpu - x_in) - upd_ref)) <= bound)
+
+
+def dev_normal_bits(shape, std: float, seed: int, mean: float = 0.0) -> torch.Tensor:
+    """Seeded N(mean, std) bf16 tensor generated ON the device (for inputs too large to draw on the
+    host).  The oracle receives the same bits through a device-to-host copy of what it needs."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(int(seed))
+    t = torch.empty(shape, dtype=torch.float32, device="cuda")
+    t.normal_(mean, std, generator=g)
+    return t.to(torch.bfloat16)
+
+
+def dev_layer_weights(shape, seed: int):
+    """One layer's parameters drawn on the device with the recipe of synth.make_layer_weights.
+    Returns (struct for the C ABI, dict of device tensors)."""
+    h, m = shape.hidden, shape.ffn
+    w = {
+        "ln1_g": dev_normal_bits((h,), 0.02, seed + 1, 1.0), "ln1_b": dev_normal_bits((h,), 0.02, seed + 2),
+        "w_qkv": dev_normal_bits((3 * h, h), 0.02, seed + 3), "b_qkv": dev_normal_bits((3 * h,), 0.02, seed + 4),
+        "w_o": dev_normal_bits((h, h), 0.02, seed + 5), "b_o": dev_normal_bits((h,), 0.02, seed + 6),
+        "ln2_g": dev_normal_bits((h,), 0.02, seed + 7, 1.0), "ln2_b": dev_normal_bits((h,), 0.02, seed + 8),
+        "w_fc1": dev_normal_bits((m, h), 0.02, seed + 9), "b_fc1": dev_normal_bits((m,), 0.02, seed + 10),
+        "w_fc2": dev_normal_bits((h, m), 0.02, seed + 11), "b_fc2": dev_normal_bits((h,), 0.02, seed + 12),
+    }
+    lw, keep = binding.Context.pack_weights(w)
+    return lw, keep
+
+
+def host_weights(wdev: dict) -> dict:
+    """Device weights -> numpy bf16 bit patterns (what the oracle consumes)."""
+    return {k: to_bits(v) for k, v in wdev.items()}
