@@ -215,6 +215,32 @@ def main():
         "migrate_hbm_frac": round(work["kv_migrate"][1] / (phase["migrate_ms"] * 1e-3) / cost.PEAK_HBM_BYTES, 4),
     }
 
+    # ---------------- extra: the KV hand-off at a size that does not fit the 256 MB last-level cache ----------------
+    extras = {}
+    if not args.small:
+        Bm, Lm = 8, 2048                      # 16384 tokens of this layer's K and V: 2 x 168 MB read + written
+        tm_ = Bm * Lm
+        ks = torch.empty(tm_, h, dtype=torch.bfloat16, device=dev).normal_()
+        vs = torch.empty(tm_, h, dtype=torch.bfloat16, device=dev).normal_()
+        btm, nblkm = synth.make_block_tables([Lm] * Bm, shape.block_size, seed + 7)
+        kcm = torch.empty(nblkm, n, shape.block_size, s, dtype=torch.bfloat16, device=dev)
+        vcm = torch.empty_like(kcm)
+        cum = torch.from_numpy(synth.cu_seqlens([Lm] * Bm)).to(dev)
+        btm_d = torch.from_numpy(btm).to(dev)
+        for _ in range(2):
+            ctx.ds_kv_migrate(ks, vs, cum, Bm, tm_, Lm, btm_d, btm.shape[1], kcm, vcm, nblkm)
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(5):
+            ctx.ds_kv_migrate(ks, vs, cum, Bm, tm_, Lm, btm_d, btm.shape[1], kcm, vcm, nblkm)
+        b.record()
+        torch.cuda.synchronize()
+        msm = a.elapsed_time(b) / 5
+        bytes_m = cost.kv_migrate_bytes(tm_, h)
+        extras["kv_migrate_16384_tokens"] = {"ms": round(msm, 4), "GB_per_s": round(bytes_m / (msm * 1e-3) / 1e9, 1),
+                                             "hbm_frac": round(bytes_m / (msm * 1e-3) / cost.PEAK_HBM_BYTES, 4)}
+        del ks, vs, kcm, vcm
+
     # ---------------- CPU oracle on a bounded sample of the same workload ----------------
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -233,6 +259,7 @@ def main():
         "phases": phases,
         "roofline": roofline,
         "kernels": kernels,
+        "extras": extras,
         "cpu_baseline": cpu_baseline,
         "setup_s": round(setup_s, 1),
     }

@@ -9,7 +9,7 @@ namespace ds {
 
 constexpr int kPage = 16;          // tokens per page
 constexpr int kMigThreads = 256;
-constexpr int kMigHeadsPerWg = 8;  // heads one workgroup moves for one page
+constexpr int kMigHeadsPerWg = 4;  // heads one workgroup moves for one page
 constexpr int kMigUnroll = 4;
 
 // grid: x = logical page index within the sequence, y = sequence,
