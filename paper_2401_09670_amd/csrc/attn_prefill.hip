@@ -17,27 +17,40 @@ namespace ds {
 constexpr int kAttThreads = 256;
 constexpr int kAttQ = 128;    // queries per workgroup
 constexpr int kAttKV = 64;    // keys per tile
+constexpr float kSlack = 8.f;   // exponent headroom before the softmax reference point is moved
 constexpr int kVtStride = kAttKV + 4;  // elements per V^T row (136 B): 8-byte reads of 16 rows hit distinct banks
 
 template <int HD>
-__global__ __launch_bounds__(kAttThreads) void prefill_attention_kernel(
+__global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))) void prefill_attention_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const int32_t* __restrict__ cu_seqlens, uint16_t* __restrict__ o, int n_heads, float scale_log2e) {
+    const int32_t* __restrict__ cu_seqlens, uint16_t* __restrict__ o, int n_heads, float scale_log2e,
+    int n_pairs, int pairs_per_xcd, int n_qt, int qt_fast) {
   constexpr int KS = HD + 8;        // K tile row stride in elements
   constexpr int DSTEPS = HD / 16;   // MFMA k-steps over the head dimension
   constexpr int DT = HD / 32;       // 32-row tiles of O^T
   __shared__ __attribute__((aligned(16))) uint16_t ks[kAttKV * KS];
   __shared__ __attribute__((aligned(16))) uint16_t vt[HD * kVtStride];
 
-  const int seq = blockIdx.z;
-  const int head = blockIdx.y;
+  // Workgroups reach the chip's eight partitions (each with its own L2) round-robin in launch
+  // order, so id % 8 names the partition and id / 8 the order inside it.  A (request, head) pair is
+  // pinned to one partition.  With few query tiles per pair the tiles are ordered heaviest first
+  // across all pairs (longest-first balances the tail); with many, the tiles of one pair run back
+  // to back so its K/V stay in that partition's L2 while they are re-read.
+  const int id = blockIdx.x;
+  const int xcd = id & 7, slot = id >> 3;
+  const int pl = qt_fast ? slot / n_qt : slot % pairs_per_xcd;
+  const int rank = qt_fast ? slot % n_qt : slot / pairs_per_xcd;
+  const int pair = pl * 8 + xcd;
+  if (pair >= n_pairs) return;
+  const int seq = pair / n_heads;
+  const int head = pair - seq * n_heads;
   const int start = cu_seqlens[seq];
   const int len = cu_seqlens[seq + 1] - start;
-  // heaviest query tiles (most keys) first
-  const int q0 = ((int)gridDim.x - 1 - (int)blockIdx.x) * kAttQ;
+  const int q0 = (n_qt - 1 - rank) * kAttQ;  // heaviest query tile (most keys) first
   if (q0 >= len) return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int hl = lane >> 5, lq = lane & 31;
   const size_t h = (size_t)n_heads * HD;
   const uint16_t* kbase = k + (size_t)start * h + (size_t)head * HD;
@@ -64,41 +77,63 @@ __global__ __launch_bounds__(kAttThreads) void prefill_attention_kernel(
   const int kv_end = min(len, q0 + kAttQ);  // keys any query of this workgroup may see
   const int n_tiles = (kv_end + kAttKV - 1) / kAttKV;
 
+  // K/V tiles are fetched one tile ahead into registers, so the global-memory latency of tile i+1
+  // is covered by the matrix work of tile i.
+  constexpr int CPR = HD / 8;                                  // 16-byte chunks per K/V row
+  constexpr int KITER = kAttKV * CPR / kAttThreads;            // K chunks per thread per tile
+  constexpr int VITER = (kAttKV / 2) * CPR / kAttThreads;      // V items (2 keys x 8 dims) per thread per tile
+  u32x4 kreg[KITER], vreg0[VITER], vreg1[VITER];
+  const int krow = tid / CPR, kch = tid % CPR;                 // K: this thread's row (+ 16 i) and chunk
+  const int vpair = tid % (kAttKV / 2), vch = tid / (kAttKV / 2);  // V: key pair and chunk (+ 8 i)
+  auto fetch = [&](int kv0) {
+    if (kv0 + kAttKV <= len) {  // whole tile inside the request: plain strided addresses
+      const uint16_t* kp = kbase + (size_t)(kv0 + krow) * h + kch * 8;
+#pragma unroll
+      for (int i = 0; i < KITER; ++i) kreg[i] = ld16(kp + (size_t)i * (kAttThreads / CPR) * h);
+      const uint16_t* vp = vbase + (size_t)(kv0 + 2 * vpair) * h + vch * 8;
+#pragma unroll
+      for (int i = 0; i < VITER; ++i) {
+        vreg0[i] = ld16(vp + i * (kAttThreads / (kAttKV / 2)) * 8);
+        vreg1[i] = ld16(vp + h + i * (kAttThreads / (kAttKV / 2)) * 8);
+      }
+    } else {  // ragged tail: rows past the end repeat the last key (they are masked out below)
+#pragma unroll
+      for (int i = 0; i < KITER; ++i)
+        kreg[i] = ld16(kbase + (size_t)min(kv0 + krow + i * (kAttThreads / CPR), len - 1) * h + kch * 8);
+#pragma unroll
+      for (int i = 0; i < VITER; ++i) {
+        const int ch = vch + i * (kAttThreads / (kAttKV / 2));
+        vreg0[i] = ld16(vbase + (size_t)min(kv0 + 2 * vpair, len - 1) * h + ch * 8);
+        vreg1[i] = ld16(vbase + (size_t)min(kv0 + 2 * vpair + 1, len - 1) * h + ch * 8);
+      }
+    }
+  };
+  fetch(0);
+
   for (int tile = 0; tile < n_tiles; ++tile) {
     const int kv0 = tile * kAttKV;
     __syncthreads();  // previous tile's LDS reads are done
     // ---- stage K tile [64][HD] row-major ----
-    {
-      constexpr int CPR = HD / 8;  // chunks per row
-      constexpr int ITER = kAttKV * CPR / kAttThreads;
 #pragma unroll
-      for (int i = 0; i < ITER; ++i) {
-        const int c = tid + i * kAttThreads;
-        const int r = c / CPR, ch = c % CPR;
-        const int key = min(kv0 + r, len - 1);
-        st16(ks + r * KS + ch * 8, ld16(kbase + (size_t)key * h + ch * 8));
+    for (int i = 0; i < KITER; ++i) {
+      const int c = tid + i * kAttThreads;
+      const int r = c / CPR, ch = c % CPR;
+      st16(ks + r * KS + ch * 8, kreg[i]);
+    }
+    // ---- stage V tile transposed: vt[d][key]; a thread holds two adjacent keys x 8 dims ----
+#pragma unroll
+    for (int i = 0; i < VITER; ++i) {
+      const int c = tid + i * kAttThreads;
+      const int pair = c % (kAttKV / 2), ch = c / (kAttKV / 2);
+      const u32x4 a = vreg0[i], b = vreg1[i];
+      uint32_t* dst = reinterpret_cast<uint32_t*>(vt + (ch * 8) * kVtStride + 2 * pair);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        dst[(2 * j) * (kVtStride / 2)] = (a[j] & 0xffffu) | (b[j] << 16);
+        dst[(2 * j + 1) * (kVtStride / 2)] = (a[j] >> 16) | (b[j] & 0xffff0000u);
       }
     }
-    // ---- stage V tile transposed: vt[d][key]; a thread takes two adjacent keys x 8 dims ----
-    {
-      constexpr int CPR = HD / 8;
-      constexpr int ITEMS = (kAttKV / 2) * CPR;
-      constexpr int ITER = ITEMS / kAttThreads;
-#pragma unroll
-      for (int i = 0; i < ITER; ++i) {
-        const int c = tid + i * kAttThreads;
-        const int pair = c % (kAttKV / 2), ch = c / (kAttKV / 2);
-        const int key0 = min(kv0 + 2 * pair, len - 1), key1 = min(kv0 + 2 * pair + 1, len - 1);
-        const u32x4 a = ld16(vbase + (size_t)key0 * h + ch * 8);
-        const u32x4 b = ld16(vbase + (size_t)key1 * h + ch * 8);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(vt + (ch * 8) * kVtStride + 2 * pair);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          dst[(2 * j) * (kVtStride / 2)] = (a[j] & 0xffffu) | (b[j] << 16);
-          dst[(2 * j + 1) * (kVtStride / 2)] = (a[j] >> 16) | (b[j] & 0xffff0000u);
-        }
-      }
-    }
+    fetch(min(kv0 + kAttKV, (n_tiles - 1) * kAttKV));  // next tile (the last iteration re-fetches its own)
     __syncthreads();
     if (kv0 > qw0 + 31) continue;  // every key of this tile is in the future of this wave's queries
 
@@ -116,38 +151,47 @@ __global__ __launch_bounds__(kAttThreads) void prefill_attention_kernel(
       }
     }
     // ---- causal mask + running softmax; element r of tile u is key kv0 + 32u + 8(r/4) + 4hl + r%4 ----
-    const bool need_mask = (kv0 + kAttKV - 1 > qw0);
+    // Only a tile that reaches past the wave's first query needs the mask (wave-uniform choice).
+    if (kv0 + kAttKV - 1 > qw0) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kv0 + u * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
+          if (key > my_q) sacc[u][r] = -INFINITY;
+        }
+    }
     float tmax = -INFINITY;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (need_mask) {
-          const int key = kv0 + u * 32 + (r >> 2) * 8 + hl * 4 + (r & 3);
-          if (key > my_q) sacc[u][r] = -INFINITY;
-        }
-        tmax = fmaxf(tmax, sacc[u][r]);
-      }
+      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[u][r]);
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(m_run, tmax);  // finite: key kv0=0 is visible to every query
-    const float alpha = exp2f((m_run - m_new) * scale_log2e);
-    const float mb = m_new * scale_log2e;
+    // The reference point m_run of the exponentials only has to keep them in range, so it is moved
+    // (and the accumulators rescaled) only when some query's maximum grew by more than kSlack in
+    // the exponent: probabilities then stay below 2^kSlack and the final quotient is unchanged.
+    if (__builtin_amdgcn_ballot_w64(tmax * scale_log2e > m_run * scale_log2e + kSlack) != 0) {
+      const float m_new = fmaxf(m_run, tmax);  // finite: key kv0 is visible to every query of the wave
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
+      l_run *= alpha;
+      m_run = m_new;
+#pragma unroll
+      for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
+    }
+    const float mb = m_run * scale_log2e;
     float psum = 0.f;
     bf16x8 pf[4];  // pf[2u+v]: column operand of PV step (u,v)
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float pv = exp2f(sacc[u][r] * scale_log2e - mb);
+        const float pv = __builtin_amdgcn_exp2f(sacc[u][r] * scale_log2e - mb);
         psum += pv;
         pf[2 * u + (r >> 3)][r & 7] = (__bf16)pv;
       }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int d = 0; d < DT; ++d)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
+    l_run += psum;
 
     // ---- O^T += V^T P^T.  PV step (u,v) contracts keys 32u+16v + {0..3, 8..11} + 4hl ----
 #pragma unroll
@@ -185,19 +229,29 @@ __global__ __launch_bounds__(kAttThreads) void prefill_attention_kernel(
   }
 }
 
+int g_attn_force_order = -1;  // development switch: 0/1 force the workgroup order, -1 choose by grid size
+
 hipError_t launch_prefill_attention(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
                                     int B, int max_seqlen, int n_heads, int head_dim, void* o,
                                     hipStream_t stream) {
   if (B <= 0 || max_seqlen <= 0) return hipSuccess;
-  if (B > 65535 || n_heads > 65535) return hipErrorInvalidValue;
-  const dim3 grid((max_seqlen + kAttQ - 1) / kAttQ, n_heads, B);
+  const int n_qt = (max_seqlen + kAttQ - 1) / kAttQ;
+  const long n_pairs = (long)B * n_heads;
+  const long pairs_per_xcd = (n_pairs + 7) / 8;
+  const long wgs = 8 * pairs_per_xcd * n_qt;
+  if (wgs > 0x7fffffffL) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)wgs);
+  // all resident at once (two workgroups per compute unit, 256 units) or close to it: balance; else locality
+  const int qt_fast = g_attn_force_order >= 0 ? g_attn_force_order : (wgs > 2 * 512 ? 1 : 0);
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
   if (head_dim == 128) {
     hipLaunchKernelGGL(prefill_attention_kernel<128>, grid, dim3(kAttThreads), 0, stream, (const uint16_t*)q,
-                       (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, scale_log2e);
+                       (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, scale_log2e,
+                       (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast);
   } else if (head_dim == 64) {
     hipLaunchKernelGGL(prefill_attention_kernel<64>, grid, dim3(kAttThreads), 0, stream, (const uint16_t*)q,
-                       (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, scale_log2e);
+                       (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, scale_log2e,
+                       (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast);
   } else {
     return hipErrorInvalidValue;
   }
