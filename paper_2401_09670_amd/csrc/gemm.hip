@@ -182,6 +182,41 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   using all_loads = std::integral_constant<int, LPS>;
   auto no_mem = [](int) {};
 
+  // ---- epilogue set-up (used after the k-loop; the first pass's loads are issued inside it) ----
+  // Each wave stages its own WTM x (GA*32) fp32 block (GA column tiles per pass) in LDS that the
+  // k-loop no longer needs; rows are padded by 4 floats so the 16-byte transposing writes of 16
+  // lanes fall into distinct banks.
+  constexpr int LDS_FLOATS = STAGES * STAGE_ELEMS / 2;
+  constexpr int GA_FIT = (LDS_FLOATS / (4 * WTM) - 4) / 32;
+  constexpr int GA = GA_FIT < TN ? GA_FIT : TN;
+  static_assert(GA >= 1, "no room to stage the epilogue");
+  constexpr int RSTR = GA * 32 + 4;  // staging row stride in floats
+  constexpr int MAX_ITERS = WTM * GA * 4 / 64;
+  constexpr int NPASS = (TN + GA - 1) / GA;
+  const int row_base = m0 + wm * WTM;
+  const int col_base = n0 + wn * WTN;
+  // Pass `a0/GA` covers column tiles a0 .. a0+ga-1; after the LDS transposition lane `idx = it*64+lane`
+  // owns row idx / cpr, 8-column chunk idx % cpr (cpr = 4*ga chunks per row).
+  u32x4 epi_res[2][MAX_ITERS], epi_bias[2][MAX_ITERS];
+  auto epi_prefetch = [&](int a0, u32x4* resv, u32x4* biasv) {
+    const int ga = (TN - a0) < GA ? (TN - a0) : GA;
+    const int cpr = ga * 4;
+    const int iters = WTM * cpr / 64;
+#pragma unroll
+    for (int it = 0; it < MAX_ITERS; ++it) {
+      if (it >= iters) break;
+      const int idx = it * 64 + lane;
+      const int r = idx / cpr, ch = idx - r * cpr;
+      const int row = row_base + r, n = col_base + a0 * 32 + ch * 8;
+      const bool ok = row < p.M && n < p.N;
+      resv[it] = u32x4{0, 0, 0, 0};
+      biasv[it] = u32x4{0, 0, 0, 0};
+      if (ok && p.residual) resv[it] = ld16(p.residual + (size_t)row * p.N + n);
+      // when cpr divides 64 the chunk (hence the bias piece) is the same for every `it`
+      if (ok && p.bias && (it == 0 || 64 % cpr != 0)) biasv[it] = ld16(p.bias + n);
+    }
+  };
+
   {
     // Direct-to-LDS schedule (3 LDS buffers, ONE barrier per k-tile, two k-tiles of flight time):
     //   iteration kt:  first half of tile kt (fetching the fragments of its second half)
@@ -200,7 +235,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
     for (int r = 0; r < NR; ++r) frag_read(fa, lds, 0, r);
 
     int stage = 0;  // buffer of tile kt
-    for (int kt = 0; kt < KT; ++kt) {
+    for (int kt = 0; kt < KT - 1; ++kt) {
       const uint16_t* sb = lds + stage * STAGE_ELEMS;
       int nstage = stage + 1;
       if (nstage == STAGES) nstage = 0;
@@ -209,9 +244,19 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
       half(none{}, fa, fb, sb, 2, no_mem);
       wait_vmcnt<LPS>();
       __syncthreads();
-      // (past the last tile the fragment fetch reads a stale buffer; the values are never used)
       half(all_loads{}, fb, fa, sbn, 0, [&](int j) { issue_one(stage, kt + 3, j); });
       stage = nstage;
+    }
+    // Last k-tile (already in LDS and visible since the previous iteration's barrier): no loads, no
+    // waits.  The residual and bias pieces of the first epilogue pass are requested before it, so
+    // their memory latency passes while the matrix pipe still has work.
+    epi_prefetch(0, epi_res[0], epi_bias[0]);
+    {
+      const uint16_t* sb = lds + stage * STAGE_ELEMS;
+      __builtin_amdgcn_sched_barrier(0);
+      half(none{}, fa, fb, sb, 2, no_mem);
+      // (the fragment fetch of this half reads a buffer of clamped re-loads; the values are never used)
+      half(none{}, fb, fa, sb, 0, no_mem);
     }
     wait_vmcnt<0>();  // the clamped re-loads of the loop tail must not land in the epilogue's staging area
   }
@@ -221,20 +266,16 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   // Each wave stages its own WTM x (GA*32) fp32 block (GA column tiles per pass) in LDS that the
   // k-loop no longer needs; rows are padded by 4 floats so the 16-byte transposing writes of 16
   // lanes fall into distinct banks.
-  constexpr int LDS_FLOATS = STAGES * STAGE_ELEMS / 2;
-  constexpr int GA_FIT = (LDS_FLOATS / (4 * WTM) - 4) / 32;
-  constexpr int GA = GA_FIT < TN ? GA_FIT : TN;
-  static_assert(GA >= 1, "no room to stage the epilogue");
-  constexpr int RSTR = GA * 32 + 4;  // staging row stride in floats
   __syncthreads();                 // every wave has finished reading the k-loop buffers
   float* stg = reinterpret_cast<float*>(lds) + wave * (WTM * RSTR);
-  const int row_base = m0 + wm * WTM;
-  const int col_base = n0 + wn * WTN;
 #pragma unroll
-  for (int a0 = 0; a0 < TN; a0 += GA) {
-    constexpr int kDummy = 0;
-    (void)kDummy;
+  for (int pass = 0; pass < NPASS; ++pass) {
+    const int a0 = pass * GA;
     const int ga = (TN - a0) < GA ? (TN - a0) : GA;  // column tiles in this pass (compile-time after unrolling)
+    u32x4* resv = epi_res[pass & 1];
+    u32x4* biasv = epi_bias[pass & 1];
+    // the next pass's residual / bias pieces travel while this pass is transposed and stored
+    if (pass + 1 < NPASS) epi_prefetch(a0 + GA, epi_res[(pass + 1) & 1], epi_bias[(pass + 1) & 1]);
     // 1. accumulators -> LDS (transposing): lane holds rows b*32 + lane%32, columns a*32 + 8g + 4*(lane/32) + 0..3
 #pragma unroll
     for (int a = 0; a < GA; ++a) {
@@ -252,20 +293,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
     // 2. read back row-contiguous: chunk = 8 columns; cpr chunks per row
     const int cpr = ga * 4;
     const int iters = WTM * cpr / 64;
-    constexpr int MAX_ITERS = WTM * GA * 4 / 64;
-    u32x4 resv[MAX_ITERS], biasv[MAX_ITERS];
-#pragma unroll
-    for (int it = 0; it < MAX_ITERS; ++it) {
-      if (it >= iters) break;
-      const int idx = it * 64 + lane;
-      const int r = idx / cpr, ch = idx - r * cpr;
-      const int row = row_base + r, n = col_base + a0 * 32 + ch * 8;
-      const bool ok = row < p.M && n < p.N;
-      resv[it] = u32x4{0, 0, 0, 0};
-      biasv[it] = u32x4{0, 0, 0, 0};
-      if (ok && p.residual) resv[it] = ld16(p.residual + (size_t)row * p.N + n);
-      if (ok && p.bias) biasv[it] = ld16(p.bias + n);
-    }
 #pragma unroll
     for (int it = 0; it < MAX_ITERS; ++it) {
       if (it >= iters) break;
@@ -274,12 +301,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
       const int row = row_base + r, n = col_base + a0 * 32 + ch * 8;
       const floatx4 lo = *reinterpret_cast<const floatx4*>(stg + r * RSTR + ch * 8);
       const floatx4 hi = *reinterpret_cast<const floatx4*>(stg + r * RSTR + ch * 8 + 4);
+      const u32x4 bv = biasv[(64 % cpr != 0) ? it : 0];
       float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       u32x4 o;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        float e0 = v[2 * j] + bf16_lo(biasv[it][j]);
-        float e1 = v[2 * j + 1] + bf16_hi(biasv[it][j]);
+        float e0 = v[2 * j] + bf16_lo(bv[j]);
+        float e1 = v[2 * j + 1] + bf16_hi(bv[j]);
         if (p.relu) {
           e0 = fmaxf(e0, 0.f);
           e1 = fmaxf(e1, 0.f);
