@@ -241,6 +241,35 @@ def main():
                                              "hbm_frac": round(bytes_m / (msm * 1e-3) / cost.PEAK_HBM_BYTES, 4)}
         del ks, vs, kcm, vcm
 
+        # The prefill GEMM under sustained load with N(0,1)-like operands versus all-zero operands of
+        # the same shape: the instruction stream is identical, only the switching activity (hence the
+        # power draw and the clock the chip sustains) differs.
+        tq = sum(lens)
+        yq = torch.empty(tq, 3 * h, dtype=torch.bfloat16, device=dev)
+        for name, fill in (("random", None), ("zero", 0.0)):
+            xg = torch.empty(tq, h, dtype=torch.bfloat16, device=dev)
+            wg = torch.empty(3 * h, h, dtype=torch.bfloat16, device=dev)
+            if fill is None:
+                xg.normal_()
+                wg.normal_(0.0, 0.02)
+            else:
+                xg.zero_()
+                wg.zero_()
+            for _ in range(5):
+                ctx.ds_linear(xg, wg, None, None, 0, tq, h, 3 * h, yq)
+            a, b = ev(), ev()
+            a.record()
+            for _ in range(20):
+                ctx.ds_linear(xg, wg, None, None, 0, tq, h, 3 * h, yq)
+            b.record()
+            torch.cuda.synchronize()
+            msg = a.elapsed_time(b) / 20
+            fl = 2.0 * tq * h * 3 * h
+            extras["gemm_qkv_%s_operands" % name] = {"ms": round(msg, 4), "TFLOP_per_s": round(fl / (msg * 1e-3) / 1e12, 1),
+                                                     "mfma_frac": round(fl / (msg * 1e-3) / cost.PEAK_BF16_FLOPS, 4)}
+            del xg, wg
+        del yq
+
     # ---------------- CPU oracle on a bounded sample of the same workload ----------------
     cpu_baseline = None
     if not args.no_cpu_baseline:
