@@ -270,6 +270,28 @@ def main():
             del xg, wg
         del yq
 
+        # The token loop's exit (final LayerNorm + logits over OPT's 50272-entry vocabulary + greedy
+        # choice) for the decode batch: one more weight-streaming pass, priced like the decode GEMMs.
+        vocab = 50272
+        wv = torch.empty(vocab, h, dtype=torch.bfloat16, device=dev).normal_(0.0, 0.02)
+        xn = torch.empty(B_dec, h, dtype=torch.bfloat16, device=dev).normal_()
+        tok = torch.empty(B_dec, dtype=torch.int32, device=dev)
+        ws_tok = torch.empty(ctx.ds_next_token_workspace_bytes(B_dec, vocab), dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            ctx.ds_next_token(xn, None, B_dec, wdev["ln1_g"], wdev["ln1_b"], wv, vocab, tok, None, ws_tok)
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(20):
+            ctx.ds_next_token(xn, None, B_dec, wdev["ln1_g"], wdev["ln1_b"], wv, vocab, tok, None, ws_tok)
+        b.record()
+        torch.cuda.synchronize()
+        mst = a.elapsed_time(b) / 20
+        bytes_t = 2.0 * vocab * h + 2 * 2.0 * B_dec * h + 8.0 * B_dec
+        extras["next_token_b%d_vocab%d" % (B_dec, vocab)] = {
+            "ms": round(mst, 4), "GB_per_s": round(bytes_t / (mst * 1e-3) / 1e9, 1),
+            "hbm_frac": round(bytes_t / (mst * 1e-3) / cost.PEAK_HBM_BYTES, 4)}
+        del wv, xn
+
     # ---------------- CPU oracle on a bounded sample of the same workload ----------------
     cpu_baseline = None
     if not args.no_cpu_baseline:

@@ -143,6 +143,37 @@ ds_status ds_linear(ds_ctx *ctx, const void *x, const void *w, const void *bias,
                     const void *residual, int32_t relu, int32_t rows, int32_t in_f, int32_t out_f,
                     void *y, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- the two ends of the token loop around the layer stack ----
+ * Sec. 2.1 describes the loop these close: the prompt's tokens enter the layer
+ * stack, the prefill pass yields the first new token, each decoding step one
+ * more.  Neither call belongs to a layer; the caller runs ds_embed before the
+ * first layer and ds_next_token after the last. */
+
+/* x[r,:] = tok_emb[token_ids[r],:] + pos_emb[positions[r],:]   (fp32 sum, bf16
+ * result; OPT, the model family of Sec. 6.1, uses a learned position table).
+ * token_ids, positions: device int32 [rows]; tok_emb device bf16 [vocab,h];
+ * pos_emb device bf16 [n_pos,h] or NULL (then positions may be NULL and no
+ * position row is added); x device bf16 [rows,h].  Ids outside the tables are
+ * clamped into them (never a wild read). */
+ds_status ds_embed(ds_ctx *ctx, const int32_t *token_ids, const int32_t *positions,
+                   const void *tok_emb, int32_t vocab, const void *pos_emb, int32_t n_pos,
+                   int32_t rows, void *x, void *stream);
+
+/* Greedy choice of the next token for `rows` (<= 256) hidden rows:
+ *   a = LN(x[row_index[r],:]; ln_g, ln_b)  (bf16, as inside a layer),
+ *   logits[r,:] = a w_vocab^T              (fp32 accumulation, never stored),
+ *   next_token[r] = argmax over the vocab, ties -> lowest id.
+ * x device bf16 [x_rows,h]; row_index device int32 [rows] or NULL (rows 0..rows-1):
+ * after a packed prefill the last position of each prompt, cu_seqlens[i+1]-1;
+ * w_vocab device bf16 [vocab,h] (OPT ties it to tok_emb); vocab % 8 == 0;
+ * next_token device int32 [rows]; best_logit device fp32 [rows] or NULL.
+ * Entries of row_index are not validated. */
+size_t ds_next_token_workspace_bytes(const ds_ctx *ctx, int32_t rows, int32_t vocab);
+ds_status ds_next_token(ds_ctx *ctx, const void *x, const int32_t *row_index, int32_t rows,
+                        const void *ln_g, const void *ln_b, const void *w_vocab, int32_t vocab,
+                        int32_t *next_token, float *best_logit, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
 /* Per-request causal attention over packed q,k,v [t,n,s] -> o [t,n,s] (App. A.2). */
 ds_status ds_prefill_attention(ds_ctx *ctx, const void *q, const void *k, const void *v,
                                const int32_t *cu_seqlens, int32_t B, int32_t t, int32_t max_seqlen,
@@ -161,7 +192,8 @@ ds_status ds_decode_attention(ds_ctx *ctx, const void *q, const int32_t *kv_lens
 enum {
   DS_K_LAYERNORM = 0, DS_K_GEMM = 1, DS_K_PREFILL_ATTN = 2, DS_K_KV_MIGRATE = 3,
   DS_K_SKINNY_GEMM = 4 /* incl. its split-K reduce */, DS_K_DECODE_ATTN = 5 /* incl. split merge */,
-  DS_K_KV_APPEND = 6, DS_K_COUNT = 7
+  DS_K_KV_APPEND = 6, DS_K_TOKEN_IO = 7 /* embedding gather; the logits GEMM + greedy-choice merge */,
+  DS_K_COUNT = 8
 };
 /* Turn timing on/off.  When on, every launch is bracketed by events on the
  * caller's stream (this serialises nothing, but adds event overhead). */

@@ -27,6 +27,10 @@ What it computes (numpy, float64 unless ``dtype`` says otherwise):
   table from a paged cache (Sec. 5 uses PagedAttention) and must agree with it.
 * The KV hand-off (Sec. 3.3 / 4.3): a pure index map from the prefill side's
   contiguous per-token K,V rows into ``[num_blocks, n, block_size, s]`` pages.
+* The two ends of the token loop (Sec. 2.1: tokens in, one new token out per pass): ``embed``
+  (token row + learned position row, OPT being the model family of Sec. 6.1) and
+  ``next_token_logits`` / ``greedy`` (final LayerNorm, logits against the vocabulary matrix,
+  largest logit, lowest id among equals).
 * Size/traffic counts used to price the kernels, pinned to figures the paper
   prints (Sec. 3.3 KV size, Table 1 model sizes, App. A.3 decode traffic).
 
@@ -238,6 +242,46 @@ def layer_decode_cached(w: Dict[str, np.ndarray], x: np.ndarray, ctx_lens: Seque
 # ---------------------------------------------------------------------------
 # counts (sizes, flops, traffic)
 # ---------------------------------------------------------------------------
+# ---------------------------------------------------------------------------------------------
+# Token loop ends (Sec. 2.1)
+# ---------------------------------------------------------------------------------------------
+def embed(tok_emb: np.ndarray, pos_emb: Optional[np.ndarray], token_ids: Sequence[int],
+          positions: Optional[Sequence[int]]) -> np.ndarray:
+    """x[r] = tok_emb[token_ids[r]] + pos_emb[positions[r]] (no position term without a table)."""
+    x = np.array([tok_emb[int(i)] for i in token_ids], dtype=tok_emb.dtype)
+    if pos_emb is not None:
+        x = x + np.array([pos_emb[int(j)] for j in positions], dtype=pos_emb.dtype)
+    return x
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest value with an 8-bit significand (1 implicit + 7 stored bits), ties to even; same dtype
+    out.  Written with frexp/rint so that it does not share the bit tricks of any other rounding
+    routine in this repository.  (Finite normal-range inputs; that is all the tests feed it.)"""
+    x = np.asarray(x)
+    mant, expo = np.frexp(x.astype(np.float64))      # x = mant * 2**expo, 0.5 <= |mant| < 1
+    q = np.rint(mant * 256.0) / 256.0                # 8 significant bits; rint rounds ties to even
+    return np.ldexp(q, expo).astype(x.dtype)
+
+
+def next_token_logits(x_rows: np.ndarray, ln_g: np.ndarray, ln_b: np.ndarray, w_vocab: np.ndarray,
+                      eps: float = 1e-5, hidden_in_bf16: bool = True) -> np.ndarray:
+    """logits = LN(x_rows) w_vocab^T.  With ``hidden_in_bf16`` the normalised rows are rounded to
+    bf16 before the product: that is the precision in which the GPU path takes the greedy decision
+    (its LayerNorm writes bf16), and an argmax has to be compared at the decision's precision."""
+    a = layernorm(x_rows, ln_g, ln_b, eps)
+    if hidden_in_bf16:
+        a = round_to_bf16(a)
+    return a @ w_vocab.T
+
+
+def greedy(logits: np.ndarray) -> np.ndarray:
+    """Per row the id of the largest logit; among equal logits the lowest id (numpy's argmax returns
+    the first occurrence of the maximum)."""
+    return np.argmax(logits, axis=1).astype(np.int64)
+
+
+# ---------------------------------------------------------------------------------------------
 def layer_matrix_params(h: int, m: int) -> int:
     """Elements of the four weight matrices of one layer: 4h^2 + 2hm (App. A.3)."""
     return 4 * h * h + 2 * h * m

@@ -18,13 +18,14 @@ LIB_PATH = os.path.join(PKG_DIR, "libds.so")
 DS_OK = 0
 STATUS_NAMES = {0: "DS_OK", 1: "DS_ERR_INVALID_ARG", 2: "DS_ERR_UNSUPPORTED", 3: "DS_ERR_WORKSPACE",
                 4: "DS_ERR_HIP"}
-KERNEL_CLASSES = ("layernorm", "gemm", "prefill_attn", "kv_migrate", "skinny_gemm", "decode_attn", "kv_append")
+KERNEL_CLASSES = ("layernorm", "gemm", "prefill_attn", "kv_migrate", "skinny_gemm", "decode_attn", "kv_append",
+                  "token_io")
 
 # every symbol include/ds.h declares
 EXPORTS = ("ds_create", "ds_destroy", "ds_last_error", "ds_prefill_workspace_bytes",
            "ds_decode_workspace_bytes", "ds_prefill", "ds_kv_migrate", "ds_decode_step", "ds_layernorm",
            "ds_linear_workspace_bytes", "ds_linear", "ds_prefill_attention", "ds_decode_attention",
-           "ds_profile_enable", "ds_profile_collect")
+           "ds_embed", "ds_next_token_workspace_bytes", "ds_next_token", "ds_profile_enable", "ds_profile_collect")
 
 
 class DsError(RuntimeError):
@@ -84,6 +85,12 @@ def load_library() -> ctypes.CDLL:
     lib.ds_prefill_attention.restype = ctypes.c_int
     lib.ds_decode_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, i32, vp, vp, sz, vp]
     lib.ds_decode_attention.restype = ctypes.c_int
+    lib.ds_embed.argtypes = [vp, vp, vp, vp, i32, vp, i32, i32, vp, vp]
+    lib.ds_embed.restype = ctypes.c_int
+    lib.ds_next_token_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.ds_next_token_workspace_bytes.restype = sz
+    lib.ds_next_token.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    lib.ds_next_token.restype = ctypes.c_int
     lib.ds_profile_enable.argtypes = [vp, i32]
     lib.ds_profile_enable.restype = ctypes.c_int
     lib.ds_profile_collect.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -194,6 +201,20 @@ class Context:
                                                  max_blocks_per_seq, max_kv_len, _ptr(k_cache), _ptr(v_cache),
                                                  num_blocks, _ptr(o), _ptr(workspace), _nbytes(workspace),
                                                  _stream()))
+
+    # ---- the two ends of the token loop ----
+    def ds_embed(self, token_ids, positions, tok_emb, vocab: int, pos_emb, n_pos: int, rows: int, x):
+        self._check(self.lib.ds_embed(self.handle, _ptr(token_ids), _ptr(positions), _ptr(tok_emb), vocab,
+                                      _ptr(pos_emb), n_pos, rows, _ptr(x), _stream()))
+
+    def ds_next_token_workspace_bytes(self, rows: int, vocab: int) -> int:
+        return self.lib.ds_next_token_workspace_bytes(self.handle, rows, vocab)
+
+    def ds_next_token(self, x, row_index, rows: int, ln_g, ln_b, w_vocab, vocab: int, next_token, best_logit,
+                      workspace):
+        self._check(self.lib.ds_next_token(self.handle, _ptr(x), _ptr(row_index), rows, _ptr(ln_g), _ptr(ln_b),
+                                           _ptr(w_vocab), vocab, _ptr(next_token), _ptr(best_logit),
+                                           _ptr(workspace), _nbytes(workspace), _stream()))
 
     # ---- timing ----
     def ds_profile_enable(self, on: bool):

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libds.so")
 SOURCES = ["ds_api.hip", "layernorm.hip", "kv_cache.hip", "gemm.hip", "gemm_skinny.hip",
-           "attn_prefill.hip", "attn_decode.hip"]
+           "attn_prefill.hip", "attn_decode.hip", "token_io.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -229,6 +229,53 @@ ds_status ds_linear(ds_ctx* ctx, const void* x, const void* w, const void* bias,
   return linear(ctx, x, w, rows, in_f, out_f, ep, workspace, static_cast<hipStream_t>(stream));
 }
 
+ds_status ds_embed(ds_ctx* ctx, const int32_t* token_ids, const int32_t* positions, const void* tok_emb,
+                   int32_t vocab, const void* pos_emb, int32_t n_pos, int32_t rows, void* x, void* stream) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  if (!token_ids || !tok_emb || !x || rows <= 0 || vocab <= 0)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_embed: NULL pointer or non-positive size");
+  if (pos_emb && (!positions || n_pos <= 0))
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_embed: a position table needs positions and n_pos > 0");
+  if (!aligned16(tok_emb) || !aligned16(pos_emb) || !aligned16(x))
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_embed: tables and x must be 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  DS_LAUNCH(ctx, s, DS_K_TOKEN_IO,
+            ds::launch_embed(token_ids, positions, tok_emb, vocab, pos_emb, n_pos, rows, ctx->cfg.hidden, x, s));
+  return DS_OK;
+}
+
+size_t ds_next_token_workspace_bytes(const ds_ctx* ctx, int32_t rows, int32_t vocab) {
+  if (!ctx || rows <= 0 || rows > kSkinnyMaxRows || vocab <= 0) return 0;
+  const size_t a = align_up((size_t)rows * ctx->cfg.hidden * 2, 256);
+  return a + align_up(ds::skinny_argmax_workspace_bytes(rows, vocab, ctx->cfg.hidden), 256);
+}
+
+ds_status ds_next_token(ds_ctx* ctx, const void* x, const int32_t* row_index, int32_t rows, const void* ln_g,
+                        const void* ln_b, const void* w_vocab, int32_t vocab, int32_t* next_token,
+                        float* best_logit, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  if (!x || !ln_g || !ln_b || !w_vocab || !next_token || rows <= 0 || vocab <= 0)
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_next_token: NULL pointer or non-positive size");
+  if (rows > kSkinnyMaxRows)
+    return fail(ctx, DS_ERR_UNSUPPORTED, "ds_next_token: at most %d rows per call", kSkinnyMaxRows);
+  if (vocab % 8 != 0 || ctx->cfg.hidden % 128 != 0)
+    return fail(ctx, DS_ERR_UNSUPPORTED, "ds_next_token: vocab must be a multiple of 8 and hidden of 128");
+  if (!aligned16(x) || !aligned16(ln_g) || !aligned16(ln_b) || !aligned16(w_vocab) || !aligned16(workspace))
+    return fail(ctx, DS_ERR_INVALID_ARG, "ds_next_token: pointers must be 16-byte aligned");
+  const size_t need = ds_next_token_workspace_bytes(ctx, rows, vocab);
+  if (!workspace || workspace_bytes < need)
+    return fail(ctx, DS_ERR_WORKSPACE, "ds_next_token: workspace %zu < %zu", workspace_bytes, need);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Carver cv(workspace);
+  void* a = cv.take((size_t)rows * ctx->cfg.hidden * 2);
+  void* cand = cv.take(ds::skinny_argmax_workspace_bytes(rows, vocab, ctx->cfg.hidden));
+  DS_LAUNCH(ctx, s, DS_K_LAYERNORM,
+            ds::launch_layernorm(x, ln_g, ln_b, a, rows, ctx->cfg.hidden, ctx->cfg.ln_eps, s, row_index));
+  DS_LAUNCH(ctx, s, DS_K_TOKEN_IO,
+            ds::launch_skinny_argmax(a, w_vocab, rows, vocab, ctx->cfg.hidden, cand, next_token, best_logit, s));
+  return DS_OK;
+}
+
 ds_status ds_prefill_attention(ds_ctx* ctx, const void* q, const void* k, const void* v,
                                const int32_t* cu_seqlens, int32_t B, int32_t t, int32_t max_seqlen, void* o,
                                void* stream) {

@@ -39,6 +39,10 @@ struct SkinnyParams {
   int M, N, K;
   int relu;
   float* partial;  // [KSPLIT][M][N] fp32 when gridDim.y > 1
+  // Greedy-choice mode (unsplit launches only): nothing is written to `out`; per row the largest
+  // accumulator of this workgroup's columns and its column go to amax_val / amax_idx [gridDim.x][M].
+  float* amax_val = nullptr;
+  int32_t* amax_idx = nullptr;
 };
 
 template <int VM>
@@ -158,6 +162,63 @@ __global__ __launch_bounds__(kSkThreads) void skinny_gemm_kernel(const SkinnyPar
   }
 
   // acc[a][t][r]: row m = 16t + lane%16, column n = n0 + 16*(ng*NTW + a) + 4*(lane/16) + r
+  if (p.amax_val) {
+    // candidates of this lane per row tile, then across the 4 lanes that share a row (lane/16), then
+    // across the 4 column-group waves through LDS (behind the k-half buffer, which may still be read)
+    constexpr int RED_FLOATS = 4 * NTW * MT * 64 * 4;
+    float* cv = reinterpret_cast<float*>(lds) + RED_FLOATS;  // [4 waves][MT][16]
+    int32_t* ci = reinterpret_cast<int32_t*>(cv + 4 * MT * 16);
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      float bv = -INFINITY;
+      int bi = 0x7fffffff;
+#pragma unroll
+      for (int a = 0; a < NTW; ++a)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int n = n0 + (ng * NTW + a) * 16 + (lane >> 4) * 4 + r;
+          const float v = acc[a][t][r];
+          if (n < p.N && (v > bv || (v == bv && n < bi))) {
+            bv = v;
+            bi = n;
+          }
+        }
+#pragma unroll
+      for (int off = 16; off <= 32; off <<= 1) {
+        const float ov = __shfl_xor(bv, off, 64);
+        const int oi = __shfl_xor(bi, off, 64);
+        if (ov > bv || (ov == bv && oi < bi)) {
+          bv = ov;
+          bi = oi;
+        }
+      }
+      if (lane < 16) {
+        cv[(ng * MT + t) * 16 + lane] = bv;
+        ci[(ng * MT + t) * 16 + lane] = bi;
+      }
+    }
+    __syncthreads();  // the four remaining waves (the k-half-1 waves have left)
+    if (ng == 0) {
+      for (int e = lane; e < MT * 16; e += 64) {  // e = 16 t + row-in-tile = row m
+        float bv = cv[e];
+        int bi = ci[e];
+#pragma unroll
+        for (int g = 1; g < 4; ++g) {
+          const float ov = cv[g * MT * 16 + e];
+          const int oi = ci[g * MT * 16 + e];
+          if (ov > bv || (ov == bv && oi < bi)) {
+            bv = ov;
+            bi = oi;
+          }
+        }
+        if (e < p.M) {
+          p.amax_val[(size_t)blockIdx.x * p.M + e] = bv;
+          p.amax_idx[(size_t)blockIdx.x * p.M + e] = bi;
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int a = 0; a < NTW; ++a) {
     const int n = n0 + (ng * NTW + a) * 16 + (lane >> 4) * 4;
@@ -407,7 +468,7 @@ struct SkinnyPlan {
 // (<= 256 workgroups) and should fill it; among such plans take the fewest bytes through the CUs' L1:
 //   weights + (N/BN) * X (each column block re-reads the activations) + partial sums written and
 //   read back.
-static SkinnyPlan skinny_plan(int M, int N, int K) {
+static SkinnyPlan skinny_plan(int M, int N, int K, bool allow_split = true) {
   const int slabs = K / kSkKS;
   const int mp = M <= 64 ? 64 : (M <= 128 ? 128 : 256);
   SkinnyPlan best{1, 1};
@@ -419,7 +480,8 @@ static SkinnyPlan skinny_plan(int M, int N, int K) {
     if (mp == 128 && ntw > 2) continue;
     const int wgs_n = (N + bn - 1) / bn;
     for (int splits = 1; splits <= slabs && splits <= 64; ++splits) {
-      if (g_skinny_force_splits > 0 && splits != g_skinny_force_splits) continue;
+      if (!allow_split && splits > 1) break;
+      if (allow_split && g_skinny_force_splits > 0 && splits != g_skinny_force_splits) continue;
       const double wgs = (double)wgs_n * splits;
       const bool forced = g_skinny_force_splits > 0;
       if (wgs > 256.0 && splits > 1 && !forced) break;        // never split into a second round
@@ -448,7 +510,8 @@ static hipError_t launch_skinny_cfg(const SkinnyParams& p, int splits, hipStream
   constexpr int BN = 64 * NTW;
   constexpr size_t lds_bytes = (size_t)S * (MT * 16 + BN) * kSkKS * sizeof(uint16_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS");
-  static_assert((size_t)4 * NTW * MT * 64 * 16 <= lds_bytes, "k-half reduction fits the stages");
+  static_assert((size_t)4 * NTW * MT * 64 * 16 + (size_t)4 * MT * 16 * 8 <= lds_bytes,
+                "k-half reduction (and the greedy-choice candidates behind it) fit the stages");
   auto kern = skinny_gemm_kernel<MT, NTW, S>;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 64 * 1024) {
@@ -459,6 +522,52 @@ static hipError_t launch_skinny_cfg(const SkinnyParams& p, int splits, hipStream
   }
   hipLaunchKernelGGL(kern, dim3((p.N + BN - 1) / BN, splits), dim3(kSkThreads), lds_bytes, stream, p);
   return hipGetLastError();
+}
+
+static hipError_t dispatch_skinny(const SkinnyParams& p, const SkinnyPlan& pl, hipStream_t stream) {
+  // fewer than 64 rows run as 64 (clamped duplicates; the matrix cores are idle anyway)
+  if (p.M <= 64) {
+    if (pl.ntw == 4) return launch_skinny_cfg<4, 4, 2>(p, pl.splits, stream);  // 160 KB
+    if (pl.ntw == 2) return launch_skinny_cfg<4, 2, 3>(p, pl.splits, stream);  // 144 KB
+    return launch_skinny_cfg<4, 1, 2>(p, pl.splits, stream);                   //  64 KB
+  }
+  if (p.M <= 128) {
+    if (pl.ntw == 2) return launch_skinny_cfg<8, 2, 2>(p, pl.splits, stream);  // 128 KB
+    return launch_skinny_cfg<8, 1, 3>(p, pl.splits, stream);                   // 144 KB
+  }
+  return launch_skinny_cfg<16, 1, 2>(p, pl.splits, stream);                    // 160 KB
+}
+
+hipError_t launch_argmax_merge(const float* part_val, const int32_t* part_idx, int n_blocks, int M,
+                               int32_t* next_token, float* best_logit, hipStream_t stream);
+
+size_t skinny_argmax_workspace_bytes(int M, int N, int K) {
+  if (K % kSkKS != 0 || M > 256 || M <= 0 || N <= 0) return 0;
+  const SkinnyPlan pl = skinny_plan(M, N, K, false);
+  const size_t blocks = (size_t)(N + 64 * pl.ntw - 1) / (64 * pl.ntw);
+  return blocks * M * (sizeof(float) + sizeof(int32_t));
+}
+
+hipError_t launch_skinny_argmax(const void* X, const void* W, int M, int N, int K, void* workspace,
+                                int32_t* next_token, float* best_logit, hipStream_t stream) {
+  if (M <= 0 || M > 256 || N <= 0 || K % kSkKS != 0 || !workspace || !next_token) return hipErrorInvalidValue;
+  const SkinnyPlan pl = skinny_plan(M, N, K, false);
+  const int blocks = (N + 64 * pl.ntw - 1) / (64 * pl.ntw);
+  SkinnyParams p;
+  p.X = (const uint16_t*)X;
+  p.W = (const uint16_t*)W;
+  p.bias = nullptr;
+  p.residual = nullptr;
+  for (int i = 0; i < 3; ++i) p.out[i] = nullptr;
+  p.seg_cols = N;
+  p.M = M; p.N = N; p.K = K;
+  p.relu = 0;
+  p.partial = nullptr;
+  p.amax_val = (float*)workspace;
+  p.amax_idx = (int32_t*)(p.amax_val + (size_t)blocks * M);
+  hipError_t e = dispatch_skinny(p, pl, stream);
+  if (e != hipSuccess) return e;
+  return launch_argmax_merge(p.amax_val, p.amax_idx, blocks, M, next_token, best_logit, stream);
 }
 
 hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
@@ -480,18 +589,7 @@ hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K,
   const SkinnyPlan pl = skinny_plan(M, N, K);
   p.partial = (float*)workspace;
   if (pl.splits > 1 && workspace == nullptr) return hipErrorInvalidValue;
-  hipError_t e;
-  // fewer than 64 rows run as 64 (clamped duplicates; the matrix cores are idle anyway)
-  if (M <= 64) {
-    if (pl.ntw == 4) e = launch_skinny_cfg<4, 4, 2>(p, pl.splits, stream);       // 160 KB
-    else if (pl.ntw == 2) e = launch_skinny_cfg<4, 2, 3>(p, pl.splits, stream);  // 144 KB
-    else e = launch_skinny_cfg<4, 1, 2>(p, pl.splits, stream);                   //  64 KB
-  } else if (M <= 128) {
-    if (pl.ntw == 2) e = launch_skinny_cfg<8, 2, 2>(p, pl.splits, stream);       // 128 KB
-    else e = launch_skinny_cfg<8, 1, 3>(p, pl.splits, stream);                   // 144 KB
-  } else {
-    e = launch_skinny_cfg<16, 1, 2>(p, pl.splits, stream);                       // 160 KB
-  }
+  hipError_t e = dispatch_skinny(p, pl, stream);
   if (e != hipSuccess) return e;
   if (pl.splits > 1) {
     const long items = (long)M * (N / 8);

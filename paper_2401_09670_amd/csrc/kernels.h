@@ -8,8 +8,10 @@
 namespace ds {
 
 // y = LN(x) * gamma + beta, one workgroup per row.  h % 8 == 0, h <= 16384.
+// With `row_index` (device, `rows` entries) output row r normalises input row row_index[r].
 hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* out,
-                            int rows, int h, float eps, hipStream_t stream);
+                            int rows, int h, float eps, hipStream_t stream,
+                            const int32_t* row_index = nullptr);
 
 // Epilogue of both GEMM paths: out = act(acc + bias) + residual, written as bf16.
 // The N output columns may be cut into up to three equal segments of
@@ -52,6 +54,19 @@ size_t skinny_workspace_bytes(int M, int N, int K);
 hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
                               void* workspace, hipStream_t stream, const SkinnyFused* fused = nullptr,
                               bool* fused_done = nullptr);
+
+// Greedy token choice over logits = X[M,K] W[N,K]^T (M <= 256, fp32 accumulation, never written out):
+// the weight-streaming kernel keeps, per row and column block, the largest logit and its column; a
+// second kernel merges the blocks (ties -> lowest column).  next_token [M] int32, best_logit [M]
+// fp32 or null.  Workspace: skinny_argmax_workspace_bytes.
+size_t skinny_argmax_workspace_bytes(int M, int N, int K);
+hipError_t launch_skinny_argmax(const void* X, const void* W, int M, int N, int K, void* workspace,
+                                int32_t* next_token, float* best_logit, hipStream_t stream);
+
+// x[r,:] = tok_emb[clamp(token_ids[r]),:] + pos_emb[clamp(positions[r]),:] (fp32 sum, bf16 result);
+// pos_emb / positions may be null (no position term).  h % 8 == 0.
+hipError_t launch_embed(const int32_t* token_ids, const int32_t* positions, const void* tok_emb, int vocab,
+                        const void* pos_emb, int n_pos, int rows, int h, void* x, hipStream_t stream);
 
 // Causal attention within each packed request; q,k,v,o rows have `n_heads*head_dim` elements.
 hipError_t launch_prefill_attention(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,

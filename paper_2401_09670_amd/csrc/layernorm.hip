@@ -21,11 +21,13 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* __restrict__ x,
                                                                const uint16_t* __restrict__ gamma,
                                                                const uint16_t* __restrict__ beta,
-                                                               uint16_t* __restrict__ out, int h, float eps) {
+                                                               uint16_t* __restrict__ out, int h, float eps,
+                                                               const int32_t* __restrict__ row_index) {
   __shared__ float red[4];
   const int nchunk = h >> 3;
   const size_t row = blockIdx.x;
-  const uint16_t* xr = x + row * (size_t)h;
+  // output row `row` normalises input row row_index[row] (all rows in order when there is no index)
+  const uint16_t* xr = x + (row_index ? (size_t)row_index[row] : row) * (size_t)h;
   uint16_t* orow = out + row * (size_t)h;
 
   float vals[kLnMaxChunks][8];
@@ -77,11 +79,11 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
 }
 
 hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* out, int rows, int h,
-                            float eps, hipStream_t stream) {
+                            float eps, hipStream_t stream, const int32_t* row_index) {
   if (rows <= 0) return hipSuccess;
   if (h % 8 != 0 || h > kLnThreads * 8 * kLnMaxChunks) return hipErrorInvalidValue;
   hipLaunchKernelGGL(layernorm_kernel, dim3(rows), dim3(kLnThreads), 0, stream, (const uint16_t*)x,
-                     (const uint16_t*)gamma, (const uint16_t*)beta, (uint16_t*)out, h, eps);
+                     (const uint16_t*)gamma, (const uint16_t*)beta, (uint16_t*)out, h, eps, row_index);
   return hipGetLastError();
 }
 

@@ -355,3 +355,73 @@ def test_counts_match_paper_values():
         mem = n * 3 * s * l * (l / b)
         assert abs(flops / mem - float(g[key])) < 0.01
     assert orc.decode_attention_kv_elems([511, 0], 5120) == 2 * 5120 * 513
+
+
+# ---------------------------------------------------------------------------------------------
+# Token loop ends (Sec. 2.1): embedding, logits, greedy choice
+# ---------------------------------------------------------------------------------------------
+def test_embed_is_one_hot_matmul():
+    rng = np.random.default_rng(11)
+    V, P, h, rows = 37, 19, 24, 13
+    te, pe = rng.normal(size=(V, h)), rng.normal(size=(P, h))
+    ids, pos = rng.integers(0, V, size=rows), rng.integers(0, P, size=rows)
+    got = orc.embed(te, pe, ids, pos)
+    onehot_t = np.zeros((rows, V)); onehot_t[np.arange(rows), ids] = 1.0
+    onehot_p = np.zeros((rows, P)); onehot_p[np.arange(rows), pos] = 1.0
+    assert np.allclose(got, onehot_t @ te + onehot_p @ pe, rtol=0, atol=1e-14)
+    assert np.array_equal(orc.embed(te, None, ids, None), te[ids])
+    # a repeated id gives identical rows; position 0 and token 0 are ordinary entries
+    assert np.array_equal(orc.embed(te, pe, [0, 0], [0, 0])[0], te[0] + pe[0])
+
+
+def test_round_to_bf16_hand_values_and_torch():
+    # 8 significant bits: spacing 2^-7 in [1,2).  Ties go to the even neighbour.
+    cases = {1.0: 1.0, 1.0 + 2.0 ** -8: 1.0,                 # tie between 1 and 1+2^-7 -> even (1.0)
+             1.0 + 3 * 2.0 ** -8: 1.0 + 2 * 2.0 ** -7,       # tie between 1+2^-7 and 1+2^-6 -> even (1+2^-6)
+             1.0 + 2.0 ** -8 + 2.0 ** -20: 1.0 + 2.0 ** -7,  # just above the tie -> up
+             -3.14159: -3.140625, 1000.0: 1000.0, 1001.0: 1000.0, 1003.0: 1004.0, 0.1: 0.10009765625}
+    for x, want in cases.items():
+        assert orc.round_to_bf16(np.array([x]))[0] == want, x
+    rng = np.random.default_rng(12)
+    x = (rng.normal(size=5000) * np.exp(rng.uniform(-20, 20, size=5000))).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(orc.round_to_bf16(x), want)
+    assert orc.round_to_bf16(np.array([0.0]))[0] == 0.0
+
+
+def test_next_token_logits_against_torch_and_special_cases():
+    rng = np.random.default_rng(13)
+    rows, h, V = 7, 64, 101
+    x = rng.normal(size=(rows, h)); g = 1 + 0.1 * rng.normal(size=h); b = 0.1 * rng.normal(size=h)
+    w = rng.normal(size=(V, h))
+    got = orc.next_token_logits(x, g, b, w, 1e-5, hidden_in_bf16=False)
+    tx = torch.from_numpy(x)
+    want = torch.nn.functional.linear(
+        torch.nn.functional.layer_norm(tx, (h,), torch.from_numpy(g), torch.from_numpy(b), 1e-5),
+        torch.from_numpy(w)).numpy()
+    assert np.allclose(got, want, rtol=1e-11, atol=1e-11)
+    # rounding the hidden rows moves a logit by at most sum |w| * half-ulp of the hidden values
+    got_r = orc.next_token_logits(x, g, b, w, 1e-5, hidden_in_bf16=True)
+    a = orc.layernorm(x, g, b, 1e-5)
+    bound = (np.abs(a) * 2.0 ** -8) @ np.abs(w).T
+    assert np.all(np.abs(got_r - got) <= bound + 1e-12) and np.any(got_r != got)
+    # zero gain: every row normalises to the shift vector, so all rows get the same logits b w^T
+    z = orc.next_token_logits(x, np.zeros(h), b, w, 1e-5, hidden_in_bf16=False)
+    assert np.allclose(z, np.tile(b @ w.T, (rows, 1)), atol=1e-12)
+
+
+def test_greedy_brute_force_and_ties():
+    rng = np.random.default_rng(14)
+    logits = rng.normal(size=(9, 300))
+    logits[2, 17] = logits[2, 250] = 50.0            # tie -> lowest id
+    logits[3, :] = 1.0                               # all equal -> id 0
+    logits[4, 299] = 99.0                            # maximum in the last column
+    want = []
+    for r in range(logits.shape[0]):
+        best = 0
+        for j in range(1, logits.shape[1]):
+            if logits[r, j] > logits[r, best]:
+                best = j
+        want.append(best)
+    got = orc.greedy(logits)
+    assert got.tolist() == want and got[2] == 17 and got[3] == 0 and got[4] == 299
