@@ -185,3 +185,23 @@ def test_two_layer_stack_end_to_end(gpu):
         torch.cuda.synchronize()
         assert gu.rel_err(gu.to_f64(xg), xo) < TOL, j
         cl = cl + 1
+
+
+@pytest.mark.parametrize("name,hidden,n_heads,ffn", [
+    ("opt13b-tp2", 2560, 20, 10240),    # OPT-13B with h, n, m divided by 2
+    ("opt66b-tp4", 2304, 18, 9216),     # OPT-66B with h, n, m divided by 4
+])
+def test_tensor_parallel_shard_shapes(gpu, name, hidden, n_heads, ffn):
+    """The shapes one tensor-parallel shard works on under the paper's convention (App. A.1: with tensor
+    parallelism h, n and m are divided by the parallel degree): widths that are not multiples of the
+    GEMM tiles, on a ragged prefill batch, its hand-off and a 48-wide decode batch.  No collective is
+    involved; this is the single shard's arithmetic only."""
+    shape = synth.ModelShape(hidden=hidden, n_heads=n_heads, head_dim=128, ffn=ffn)
+    seed = 4242 + hidden
+    lw, wdev = gu.dev_layer_weights(shape, seed)
+    w32 = orc.weights_from_bits(gu.host_weights(wdev), np.float32)
+    lens = [700, 129, 1, 512, 33]
+    ctx, k_out, v_out = _prefill_and_check(shape, lw, w32, lens, seed, [0, 2, 4])
+    _migrate_and_check(ctx, shape, k_out, v_out, lens, seed)
+    ctxs = synth.uniform_lengths(48, 1, 900, seed, stream=3)
+    _decode_and_check(shape, lw, w32, ctxs, seed, [0, int(np.argmax(ctxs)), int(np.argmin(ctxs))], steps=2)
