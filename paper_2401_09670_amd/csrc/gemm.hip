@@ -4,9 +4,9 @@
 // 16-byte LDS read.  The tile is computed transposed (weight rows as the MFMA
 // row operand, activation rows as the column operand).
 //
-// Tile BM x BN (activation rows x weight rows), BK = 64, 256 threads = 4 waves
-// (one per SIMD).  Operands go global -> LDS directly (no register staging),
-// three LDS buffers, one barrier per k-tile; fragment reads and load issue are
+// Tile BM x BN (activation rows x weight rows: 256x160, 256x256 or 128x128), BK = 64,
+// 256 threads = 4 waves (one per SIMD).  Operands go global -> LDS directly (no register
+// staging), three LDS buffers (two for the 256x256 tile), one barrier per k-tile; fragment reads and load issue are
 // interleaved with the MFMAs by hand (scheduling fences); the epilogue is
 // staged through LDS so bias / residual / output move as 16-byte row pieces.
 #include <type_traits>
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   constexpr int XL = BM / 32;                             // X loads per wave per stage
   constexpr int WL = BN / 32;                             // W loads per wave per stage
   constexpr int LPS = XL + WL;
-  static_assert(2 * LPS < 64, "vmcnt range");
+  static_assert((STAGES - 1) * LPS < 64, "vmcnt range");
 
   extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
 
@@ -219,17 +219,19 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
 
   {
     // Direct-to-LDS schedule (3 LDS buffers, ONE barrier per k-tile, two k-tiles of flight time):
+    //   (written for STAGES = 3; see below for 2)
     //   iteration kt:  first half of tile kt (fetching the fragments of its second half)
     //                  wait until this wave's part of tile kt+1 has landed (tile kt+2 may still fly)
     //                  barrier: tile kt+1 is visible to all, and nobody reads buffer kt%3 any more
     //                           (the second half's fragments are already in registers)
     //                  second half of tile kt, issuing the loads of tile kt+3 into buffer kt%3 and
     //                  fetching the first-half fragments of tile kt+1
-    static_assert(STAGES == 3, "the schedule is written for 3 buffers");
-    issue(0, 0);
-    issue(1, 1);
-    issue(2, 2);
-    wait_vmcnt<2 * LPS>();
+    // With two buffers the same schedule holds with one k-tile of flight time: at the barrier tile
+    // kt+1 (requested during the second half of tile kt-1) must have landed completely.
+    static_assert(STAGES == 2 || STAGES == 3, "the schedule is written for 2 or 3 buffers");
+#pragma unroll
+    for (int st = 0; st < STAGES; ++st) issue(st, st);
+    wait_vmcnt<(STAGES - 1) * LPS>();
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < NR; ++r) frag_read(fa, lds, 0, r);
@@ -242,15 +244,17 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
       const uint16_t* sbn = lds + nstage * STAGE_ELEMS;
       __builtin_amdgcn_sched_barrier(0);
       half(none{}, fa, fb, sb, 2, no_mem);
-      wait_vmcnt<LPS>();
+      wait_vmcnt<(STAGES - 2) * LPS>();
       __syncthreads();
-      half(all_loads{}, fb, fa, sbn, 0, [&](int j) { issue_one(stage, kt + 3, j); });
+      half(all_loads{}, fb, fa, sbn, 0, [&](int j) { issue_one(stage, kt + STAGES, j); });
       stage = nstage;
     }
     // Last k-tile (already in LDS and visible since the previous iteration's barrier): no loads, no
     // waits.  The residual and bias pieces of the first epilogue pass are requested before it, so
     // their memory latency passes while the matrix pipe still has work.
-    epi_prefetch(0, epi_res[0], epi_bias[0]);
+    // (only where the register file has room for them next to the accumulators and both fragment sets)
+    constexpr bool EARLY_EPI = TM * TN <= 10;
+    if (EARLY_EPI) epi_prefetch(0, epi_res[0], epi_bias[0]);
     {
       const uint16_t* sb = lds + stage * STAGE_ELEMS;
       __builtin_amdgcn_sched_barrier(0);
@@ -258,6 +262,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
       // (the fragment fetch of this half reads a buffer of clamped re-loads; the values are never used)
       half(none{}, fb, fa, sb, 0, no_mem);
     }
+    if (!EARLY_EPI) epi_prefetch(0, epi_res[0], epi_bias[0]);
     wait_vmcnt<0>();  // the clamped re-loads of the loop tail must not land in the epilogue's staging area
   }
 
@@ -342,15 +347,20 @@ static hipError_t launch_dl(GemmParams p, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// Rounds of workgroups on 256 CUs (one workgroup per CU) times the padded tile
-// area: the cost model used to pick a tile shape.
-static double tile_cost(int M, int N, int BM, int BN) {
+// Cost model used to pick a tile shape: (rounds of workgroups on 256 CUs, one workgroup per CU) x
+// tile area x a per-area factor of the tile shape.  Under sustained matrix load the chip runs at its
+// power limit, so a partly filled last round costs less than a full one (the busy CUs clock higher):
+// only 30 % of the idle part of the last round is charged.  Factors are measured ratios of time per
+// flop: the 256x256 tile moves 23 % fewer operand bytes per flop than 256x160, the 128x128 tile 50 % more.
+static double tile_cost(int M, int N, int BM, int BN, double factor) {
   const long tiles = (long)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  const long rounds = (tiles + 255) / 256;
-  return (double)rounds * BM * BN;
+  const double exact = tiles / 256.0;
+  const double full = (double)((tiles + 255) / 256);
+  const double rounds = tiles <= 256 ? 1.0 : exact + 0.3 * (full - exact);
+  return rounds * BM * BN * factor;
 }
 
-int g_gemm_variant = 0;  // development switch (timing harness only): 0 = cost model
+int g_gemm_variant = 0;  // development switch (timing harness only): 0 = cost model, 1/2/3 force a tile
 
 hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
                        hipStream_t stream) {
@@ -370,12 +380,15 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
   int variant = g_gemm_variant;
   if (variant == 0) {
     // 256x160 quantises exactly for OPT shapes at t = 2048 (N/160 and t/256 whole, tiles a multiple of
-    // 256); the 128x128 tile wins only where the big tile would leave most of the chip idle.
-    const double big = tile_cost(M, N, 256, 160);
-    const double small = tile_cost(M, N, 128, 128) * 1.3;  // smaller tile: more operand traffic per flop
-    variant = small < big ? 2 : 1;
+    // 256); 256x256 is cheaper per flop where there are enough tiles to keep the chip full; the
+    // 128x128 tile wins only where the big tiles would leave most of the chip idle.
+    const double c1 = tile_cost(M, N, 256, 160, 1.0);
+    const double c2 = tile_cost(M, N, 128, 128, 1.3);
+    const double c3 = tile_cost(M, N, 256, 256, 0.9);
+    variant = (c3 < c1 && c3 < c2) ? 3 : (c2 < c1 ? 2 : 1);
   }
   switch (variant) {
+    case 3: return launch_dl<256, 256, 2, 2, 2>(p, stream);
     case 2: return launch_dl<128, 128, 2, 2, 3>(p, stream);
     default: return launch_dl<256, 160, 4, 1, 3>(p, stream);
   }
