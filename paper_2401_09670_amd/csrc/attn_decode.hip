@@ -64,14 +64,30 @@ __global__ __launch_bounds__(kDecThreads) void decode_attention_kernel(
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = 0.f;
 
-  for (int pg = page_lo + wave; pg < page_hi; pg += kDecWaves) {
-    const int blk = bt[pg];
-    const size_t base = ((size_t)blk * n_heads + head) * page_elems + (size_t)tg * HD + dc * 8;
-    u32x4 kr[NL], vr[NL];
+  // Software pipeline over this wave's pages: the block id is fetched two pages ahead and the K/V
+  // rows one page ahead, so neither the table lookup nor the HBM latency sits between two pages.
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const size_t lane_off = (size_t)tg * HD + dc * 8;
+  auto fetch = [&](int blk, u32x4* kd, u32x4* vd) {
+    const size_t base = ((size_t)blk * n_heads + head) * page_elems + lane_off;
 #pragma unroll
-    for (int j = 0; j < NL; ++j) kr[j] = ld16(k_cache + base + (size_t)j * TPL * HD);
+    for (int j = 0; j < NL; ++j) kd[j] = ld16(k_cache + base + (size_t)j * TPL * HD);
 #pragma unroll
-    for (int j = 0; j < NL; ++j) vr[j] = ld16(v_cache + base + (size_t)j * TPL * HD);
+    for (int j = 0; j < NL; ++j) vd[j] = ld16(v_cache + base + (size_t)j * TPL * HD);
+  };
+  u32x4 kr[NL], vr[NL], kn[NL], vn[NL];
+#pragma unroll
+  for (int j = 0; j < NL; ++j) kr[j] = vr[j] = kn[j] = vn[j] = u32x4{0, 0, 0, 0};
+  const int pg0 = page_lo + wave_u;
+  int blk1 = 0, blk2 = 0;  // block ids of the pages one and two steps ahead of `pg`
+  if (pg0 < page_hi) fetch(bt[pg0], kr, vr);
+  if (pg0 + kDecWaves < page_hi) blk1 = bt[pg0 + kDecWaves];
+  if (pg0 + 2 * kDecWaves < page_hi) blk2 = bt[pg0 + 2 * kDecWaves];
+
+  for (int pg = pg0; pg < page_hi; pg += kDecWaves) {
+    if (pg + kDecWaves < page_hi) fetch(blk1, kn, vn);
+    blk1 = blk2;
+    if (pg + 3 * kDecWaves < page_hi) blk2 = bt[pg + 3 * kDecWaves];
 
     float sc[NL];
     float tmax = -INFINITY;
@@ -104,6 +120,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_attention_kernel(
       }
     }
     m_run = m_new;
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+      kr[j] = kn[j];
+      vr[j] = vn[j];
+    }
   }
 
   // merge the token groups of the wave: every lane of a group carries the same l_run
