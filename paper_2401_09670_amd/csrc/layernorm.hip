@@ -18,6 +18,9 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return red[0] + red[1] + red[2] + red[3];
 }
 
+// NCH = 16-byte pieces per thread (row length <= NCH * 2048 elements): the row buffer is sized to the
+// row, so that short rows leave enough registers for every row of a 2048-row launch to be resident.
+template <int NCH>
 __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* __restrict__ x,
                                                                const uint16_t* __restrict__ gamma,
                                                                const uint16_t* __restrict__ beta,
@@ -30,10 +33,10 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
   const uint16_t* xr = x + (row_index ? (size_t)row_index[row] : row) * (size_t)h;
   uint16_t* orow = out + row * (size_t)h;
 
-  float vals[kLnMaxChunks][8];
+  float vals[NCH][8];
   float sum = 0.f;
 #pragma unroll
-  for (int i = 0; i < kLnMaxChunks; ++i) {
+  for (int i = 0; i < NCH; ++i) {
     const int c = threadIdx.x + i * kLnThreads;
     if (c < nchunk) {
       const u32x4 raw = ld16(xr + c * 8);
@@ -48,7 +51,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
   const float mean = block_sum(sum, red) / (float)h;
   float sq = 0.f;
 #pragma unroll
-  for (int i = 0; i < kLnMaxChunks; ++i) {
+  for (int i = 0; i < NCH; ++i) {
     const int c = threadIdx.x + i * kLnThreads;
     if (c < nchunk) {
 #pragma unroll
@@ -61,7 +64,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
   const float var = block_sum(sq, red) / (float)h;
   const float rstd = rsqrtf(var + eps);
 #pragma unroll
-  for (int i = 0; i < kLnMaxChunks; ++i) {
+  for (int i = 0; i < NCH; ++i) {
     const int c = threadIdx.x + i * kLnThreads;
     if (c < nchunk) {
       const u32x4 g = ld16(gamma + c * 8);
@@ -82,8 +85,17 @@ hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, 
                             float eps, hipStream_t stream, const int32_t* row_index) {
   if (rows <= 0) return hipSuccess;
   if (h % 8 != 0 || h > kLnThreads * 8 * kLnMaxChunks) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(layernorm_kernel, dim3(rows), dim3(kLnThreads), 0, stream, (const uint16_t*)x,
-                     (const uint16_t*)gamma, (const uint16_t*)beta, (uint16_t*)out, h, eps, row_index);
+  const int nch = ((h >> 3) + kLnThreads - 1) / kLnThreads;
+#define DS_LN_LAUNCH(N)                                                                                   \
+  hipLaunchKernelGGL(layernorm_kernel<N>, dim3(rows), dim3(kLnThreads), 0, stream, (const uint16_t*)x,   \
+                     (const uint16_t*)gamma, (const uint16_t*)beta, (uint16_t*)out, h, eps, row_index)
+  if (nch <= 1) DS_LN_LAUNCH(1);
+  else if (nch == 2) DS_LN_LAUNCH(2);
+  else if (nch == 3) DS_LN_LAUNCH(3);
+  else if (nch == 4) DS_LN_LAUNCH(4);
+  else if (nch <= 6) DS_LN_LAUNCH(6);
+  else DS_LN_LAUNCH(8);
+#undef DS_LN_LAUNCH
   return hipGetLastError();
 }
 
