@@ -93,32 +93,54 @@ struct Carver {
   }
 };
 
-// Y = act(X W^T + b) + residual for any row count: the weight-streaming kernel
-// for decode-sized batches, the MFMA tile kernel otherwise.
-bool use_skinny(int rows, int in_f) { return rows <= kSkinnyMaxRows && in_f % 128 == 0; }
+// Y = act(X W^T + b) + residual for any row count.  Up to 128 rows the weight-streaming kernel is the
+// faster one (measured with weights that do not sit in the last-level cache: 156 / 204 us against
+// 163 / 212 us for the four OPT-13B GEMMs at 32 / 128 rows); from there on the MFMA tile kernel,
+// split over K where its tiles alone would not fill the chip (287 against 364 us at 256 rows).
+// Decode-sized calls (<= 256 rows) are timed as their own class whichever kernel runs.
+constexpr int kStreamMaxRows = 128;
+bool use_skinny(int rows, int in_f) { return rows <= kStreamMaxRows && in_f % 128 == 0; }
 
 ds_status linear(ds_ctx* ctx, const void* x, const void* w, int rows, int in_f, int out_f,
-                 const ds::Epilogue& ep, void* skinny_ws, hipStream_t stream,
+                 const ds::Epilogue& ep, void* gemm_ws, hipStream_t stream,
                  const ds::SkinnyFused* fused = nullptr, bool* fused_done = nullptr) {
   if (fused_done) *fused_done = false;
-  if (use_skinny(rows, in_f)) {
-    hipError_t e;
-    {
-      Timed t(ctx, stream, DS_K_SKINNY_GEMM);
-      e = ds::launch_skinny_gemm(x, w, rows, out_f, in_f, ep, skinny_ws, stream, fused, fused_done);
-    }
-    if (e != hipSuccess) return fail(ctx, DS_ERR_HIP, "skinny gemm failed: %s", hipGetErrorString(e));
-    return DS_OK;
+  hipError_t e;
+  {
+    Timed t(ctx, stream, rows <= kSkinnyMaxRows ? DS_K_SKINNY_GEMM : DS_K_GEMM);
+    if (use_skinny(rows, in_f))
+      e = ds::launch_skinny_gemm(x, w, rows, out_f, in_f, ep, gemm_ws, stream, fused, fused_done);
+    else
+      e = ds::launch_gemm(x, w, rows, out_f, in_f, ep, stream, gemm_ws, fused, fused_done);
   }
-  DS_LAUNCH(ctx, stream, DS_K_GEMM, ds::launch_gemm(x, w, rows, out_f, in_f, ep, stream));
+  if (e != hipSuccess) return fail(ctx, DS_ERR_HIP, "gemm failed: %s", hipGetErrorString(e));
   return DS_OK;
 }
 
-size_t max_skinny_ws(const ds_model_cfg& c, int rows) {
-  size_t a = ds::skinny_workspace_bytes(rows, 3 * c.hidden, c.hidden);
-  size_t b = ds::skinny_workspace_bytes(rows, c.hidden, c.hidden);
-  size_t d = ds::skinny_workspace_bytes(rows, c.ffn, c.hidden);
-  size_t e = ds::skinny_workspace_bytes(rows, c.hidden, c.ffn);
+// split-K partials of the kernel that `linear` picks for exactly `rows` rows
+size_t linear_ws_exact(int rows, int in_f, int out_f) {
+  return use_skinny(rows, in_f) ? ds::skinny_workspace_bytes(rows, out_f, in_f)
+                                : ds::gemm_workspace_bytes(rows, out_f, in_f);
+}
+
+// ... and for any row count up to `rows` (fewer rows can mean more splits), so that a workspace sized
+// for a maximum serves every smaller call.  The plans only change with the row count rounded up to 64.
+size_t linear_ws(int rows, int in_f, int out_f) {
+  size_t need = 0;
+  for (int r = 64;; r += 64) {
+    const int rr = r < rows ? r : rows;
+    const size_t b = linear_ws_exact(rr, in_f, out_f);
+    if (b > need) need = b;
+    if (rr == rows) break;
+  }
+  return need;
+}
+
+size_t max_gemm_ws(const ds_model_cfg& c, int rows) {
+  size_t a = linear_ws(rows, c.hidden, 3 * c.hidden);
+  size_t b = linear_ws(rows, c.hidden, c.hidden);
+  size_t d = linear_ws(rows, c.hidden, c.ffn);
+  size_t e = linear_ws(rows, c.ffn, c.hidden);
   size_t m = a > b ? a : b;
   m = m > d ? m : d;
   return m > e ? m : e;
@@ -174,8 +196,8 @@ size_t ds_prefill_workspace_bytes(const ds_ctx* ctx, int32_t max_tokens) {
   const ds_model_cfg& c = ctx->cfg;
   const size_t th = align_up((size_t)max_tokens * c.hidden * 2, 256);
   const size_t tm = align_up((size_t)max_tokens * c.ffn * 2, 256);
-  // a (LN out, reused for LN2), q, o, x1, u, + skinny split-K partials for tiny batches
-  return 4 * th + tm + align_up(max_tokens <= kSkinnyMaxRows ? max_skinny_ws(c, max_tokens) : 0, 256);
+  // a (LN out, reused for LN2), q, o, x1, u, + split-K partials of the GEMMs
+  return 4 * th + tm + align_up(max_gemm_ws(c, max_tokens), 256);
 }
 
 size_t ds_decode_workspace_bytes(const ds_ctx* ctx, int32_t max_batch, int32_t max_ctx) {
@@ -185,7 +207,7 @@ size_t ds_decode_workspace_bytes(const ds_ctx* ctx, int32_t max_batch, int32_t m
   const size_t b3h = align_up((size_t)max_batch * 3 * c.hidden * 2, 256);
   const size_t bm = align_up((size_t)max_batch * c.ffn * 2, 256);
   const size_t att = align_up(ds::decode_attention_workspace_bytes(max_batch, c.n_heads, c.head_dim, max_ctx), 256);
-  const size_t sk = align_up(max_batch <= kSkinnyMaxRows ? max_skinny_ws(c, max_batch) : 0, 256);
+  const size_t sk = align_up(max_gemm_ws(c, max_batch), 256);
   // a, qkv, o, x1, u, attention partials, split-K partials
   return 3 * bh + b3h + bm + att + sk;
 }
@@ -203,7 +225,7 @@ ds_status ds_layernorm(ds_ctx* ctx, const void* x, const void* gamma, const void
 
 size_t ds_linear_workspace_bytes(const ds_ctx* ctx, int32_t rows, int32_t in_f, int32_t out_f) {
   if (!ctx || rows <= 0 || in_f <= 0 || out_f <= 0) return 0;
-  return use_skinny(rows, in_f) ? ds::skinny_workspace_bytes(rows, out_f, in_f) : 0;
+  return in_f % 64 == 0 ? linear_ws_exact(rows, in_f, out_f) : 0;
 }
 
 ds_status ds_linear(ds_ctx* ctx, const void* x, const void* w, const void* bias, const void* residual,

@@ -29,6 +29,17 @@ struct GemmParams {
   int M, N, K;
   int relu;
   int tiles_m, tiles_n;
+  // Split-K (gridDim.y > 1): split s multiplies k-tiles [KT s / S, KT (s+1) / S) and stores its fp32
+  // accumulators to partial[s][M][N]; the epilogue then belongs to whoever adds the partials.
+  float* partial;
+  // Decode QKV projection (N = 3 n_heads head_dim): with k_cache set, the K and V thirds of row m go to
+  // slot ctx_lens[m] of the paged cache [num_blocks, n_heads, 16, head_dim] instead of `out`.
+  const int32_t* ctx_lens;
+  const int32_t* block_tables;
+  int max_blocks;
+  uint16_t* k_cache;
+  uint16_t* v_cache;
+  int n_heads, head_dim;
 };
 
 // Workgroup ids are dealt round-robin to the 8 XCDs (each with a private L2).
@@ -57,7 +68,12 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((VM & 0xf) | (0x7 << 4) | (0xf << 8) | ((VM >> 4) << 14));
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+// EPI selects the epilogue at compile time, so the plain prefill instantiation carries none of the
+// decode-side code: 0 = bias / ReLU / residual -> bf16 segments; 1 = split-K, raw fp32 partials;
+// 2 = as 0, but the K and V thirds go into the paged cache.
+enum { kEpiPlain = 0, kEpiPartial = 1, kEpiKvScatter = 2 };
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int EPI>
 __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams p) {
   static_assert(WAVES_M * WAVES_N == 4, "4 waves");
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -82,7 +98,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   const int m0 = (tile % p.tiles_m) * BM;
   const int n0 = (tile / p.tiles_m) * BN;
   const int K = p.K;
-  const int KT = K / kBK;
+  const int kt_first = EPI == kEpiPartial ? (int)((long)(K / kBK) * blockIdx.y / gridDim.y) : 0;
+  const int KT = EPI == kEpiPartial ? (int)((long)(K / kBK) * (blockIdx.y + 1) / gridDim.y) - kt_first  // >= 1
+                                    : K / kBK;
 
   // per-lane source offsets (elements) of this wave's loads; load j covers rows 8*(4j+wave) .. +7
   const int lrow = lane >> 3;
@@ -103,7 +121,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   // harmless re-load into a buffer nobody reads again): this keeps the main loop free of branches, so
   // the loads can be interleaved with MFMAs by the scheduler.
   auto issue_one = [&](int stage, int kt_load, int j) {   // j in [0, LPS): X loads first, then W loads
-    const int kofs = min(kt_load, KT - 1) * kBK;
+    const int kofs = (kt_first + min(kt_load, KT - 1)) * kBK;
     uint16_t* xb = lds + stage * STAGE_ELEMS + wave_s * 512;     // 512 elements = 1 KB per wave-load
     if (j < XL) {
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.X + kofs + xoff[j]),
@@ -211,6 +229,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
       const bool ok = row < p.M && n < p.N;
       resv[it] = u32x4{0, 0, 0, 0};
       biasv[it] = u32x4{0, 0, 0, 0};
+      if (EPI == kEpiPartial) continue;
       if (ok && p.residual) resv[it] = ld16(p.residual + (size_t)row * p.N + n);
       // when cpr divides 64 the chunk (hence the bias piece) is the same for every `it`
       if (ok && p.bias && (it == 0 || 64 % cpr != 0)) biasv[it] = ld16(p.bias + n);
@@ -306,6 +325,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
       const int row = row_base + r, n = col_base + a0 * 32 + ch * 8;
       const floatx4 lo = *reinterpret_cast<const floatx4*>(stg + r * RSTR + ch * 8);
       const floatx4 hi = *reinterpret_cast<const floatx4*>(stg + r * RSTR + ch * 8 + 4);
+      if (EPI == kEpiPartial) {  // split-K: raw fp32 sums, row-contiguous
+        if (row < p.M && n < p.N) {
+          float* dst = p.partial + ((size_t)blockIdx.y * p.M + row) * p.N + n;
+          *reinterpret_cast<floatx4*>(dst) = lo;
+          *reinterpret_cast<floatx4*>(dst + 4) = hi;
+        }
+        continue;
+      }
       const u32x4 bv = biasv[(64 % cpr != 0) ? it : 0];
       float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       u32x4 o;
@@ -322,20 +349,30 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
         o[j] = pack_bf16(e0, e1);
       }
       if (row < p.M && n < p.N) {
-        const int seg = (n >= p.seg_cols) + (n >= 2 * p.seg_cols);
-        st16(p.out[seg] + (size_t)row * p.seg_cols + (n - seg * p.seg_cols), o);
+        const int hq = p.n_heads * p.head_dim;
+        if (EPI == kEpiKvScatter && n >= hq) {  // this step's new K / V row of sequence `row`: straight into its page
+          const int which = n >= 2 * hq;
+          const int col = n - hq * (1 + which);
+          const int head = col / p.head_dim, d = col - head * p.head_dim;
+          const int pos = p.ctx_lens[row];
+          const int blk = p.block_tables[(size_t)row * p.max_blocks + pos / 16];
+          st16((which ? p.v_cache : p.k_cache) + (((size_t)blk * p.n_heads + head) * 16 + (pos % 16)) * p.head_dim + d, o);
+        } else {
+          const int seg = (n >= p.seg_cols) + (n >= 2 * p.seg_cols);
+          st16(p.out[seg] + (size_t)row * p.seg_cols + (n - seg * p.seg_cols), o);
+        }
       }
     }
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
-static hipError_t launch_dl(GemmParams p, hipStream_t stream) {
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int EPI>
+static hipError_t launch_dl_epi(GemmParams p, int splits, hipStream_t stream) {
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N + BN - 1) / BN;
   constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * kBK * sizeof(uint16_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS");
-  auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, STAGES>;
+  auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -343,8 +380,15 @@ static hipError_t launch_dl(GemmParams p, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n), dim3(kGemmThreads), lds_bytes, stream, p);
+  hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n, splits), dim3(kGemmThreads), lds_bytes, stream, p);
   return hipGetLastError();
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool KV_OK>
+static hipError_t launch_dl(const GemmParams& p, int splits, hipStream_t stream) {
+  if (splits > 1) return launch_dl_epi<BM, BN, WAVES_M, WAVES_N, STAGES, kEpiPartial>(p, splits, stream);
+  if (KV_OK && p.k_cache) return launch_dl_epi<BM, BN, WAVES_M, WAVES_N, STAGES, kEpiKvScatter>(p, 1, stream);
+  return launch_dl_epi<BM, BN, WAVES_M, WAVES_N, STAGES, kEpiPlain>(p, 1, stream);
 }
 
 // Cost model used to pick a tile shape: (rounds of workgroups on 256 CUs, one workgroup per CU) x
@@ -360,12 +404,56 @@ static double tile_cost(int M, int N, int BM, int BN, double factor) {
   return rounds * BM * BN * factor;
 }
 
-int g_gemm_variant = 0;  // development switch (timing harness only): 0 = cost model, 1/2/3 force a tile
+int g_gemm_variant = 0;  // development switches (timing harness only): 0 = cost model, 1..4 force a tile
+int g_gemm_splits = 0;   // 0 = plan, > 0 force the split count
+
+struct GemmPlan {
+  int variant;  // 1: 256x160, 2: 128x128, 3: 256x256, 4: 64x128
+  int splits;
+};
+
+// Tile shape by the cost model above; split count so that a launch with few tiles still occupies the
+// chip.  Measured on the decode shapes (M <= 256): >= ~100 workgroups of 128 weight rows stream at
+// 5-6 TB/s unsplit; 40 tiles need 4-6 splits; more than ~250 workgroups gain nothing.
+static GemmPlan gemm_plan(int M, int N, int K) {
+  GemmPlan pl{1, 1};
+  if (M <= 64) {
+    pl.variant = 4;
+  } else {
+    const double c1 = tile_cost(M, N, 256, 160, 1.0);
+    const double c2 = tile_cost(M, N, 128, 128, 1.3);
+    const double c3 = tile_cost(M, N, 256, 256, 0.9);
+    pl.variant = (c3 < c1 && c3 < c2) ? 3 : (c2 < c1 ? 2 : 1);
+  }
+  if (g_gemm_variant > 0) pl.variant = g_gemm_variant;
+  const int bm = pl.variant == 4 ? 64 : (pl.variant == 2 ? 128 : 256);
+  const int bn = pl.variant == 1 ? 160 : (pl.variant == 3 ? 256 : 128);
+  const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+  const int kt = K / kBK;
+  if (tiles < 100) {
+    int s = (int)((200 + tiles / 2) / tiles);
+    const int cap = kt / 8 > 0 ? kt / 8 : 1;  // at least 8 k-tiles per split
+    if (s > cap) s = cap;
+    if (s > 32) s = 32;
+    if (s < 1) s = 1;
+    pl.splits = s;
+  }
+  if (g_gemm_splits > 0) pl.splits = g_gemm_splits < kt ? g_gemm_splits : kt;
+  return pl;
+}
+
+// Bytes of split-K partials a launch with exactly M rows needs.
+size_t gemm_workspace_bytes(int M, int N, int K) {
+  if (M <= 0 || N <= 0 || K < kBK || K % kBK != 0) return 0;
+  const GemmPlan pl = gemm_plan(M, N, K);
+  return pl.splits > 1 ? (size_t)pl.splits * M * N * sizeof(float) : 0;
+}
 
 hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
-                       hipStream_t stream) {
+                       hipStream_t stream, void* workspace, const SkinnyFused* fused, bool* fused_done) {
+  if (fused_done) *fused_done = false;
   if (M <= 0 || N <= 0) return hipSuccess;
-  if (K % kBK != 0 || N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0) return hipErrorInvalidValue;
+  if (K < kBK || K % kBK != 0 || N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0) return hipErrorInvalidValue;
   if (ep.residual && ep.seg_cols != N) return hipErrorInvalidValue;
   GemmParams p;
   p.X = (const uint16_t*)X;
@@ -377,21 +465,32 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
   p.M = M; p.N = N; p.K = K;
   p.relu = ep.relu;
   p.tiles_m = p.tiles_n = 0;
-  int variant = g_gemm_variant;
-  if (variant == 0) {
-    // 256x160 quantises exactly for OPT shapes at t = 2048 (N/160 and t/256 whole, tiles a multiple of
-    // 256); 256x256 is cheaper per flop where there are enough tiles to keep the chip full; the
-    // 128x128 tile wins only where the big tiles would leave most of the chip idle.
-    const double c1 = tile_cost(M, N, 256, 160, 1.0);
-    const double c2 = tile_cost(M, N, 128, 128, 1.3);
-    const double c3 = tile_cost(M, N, 256, 256, 0.9);
-    variant = (c3 < c1 && c3 < c2) ? 3 : (c2 < c1 ? 2 : 1);
+  p.partial = nullptr;
+  p.ctx_lens = nullptr; p.block_tables = nullptr; p.max_blocks = 0;
+  p.k_cache = nullptr; p.v_cache = nullptr; p.n_heads = 0; p.head_dim = 0;
+  GemmPlan pl = gemm_plan(M, N, K);
+  if (pl.splits > 1 && workspace == nullptr) pl.splits = 1;  // no room for partials: slower, still right
+  const bool want_kv = fused && fused->kind == SkinnyFused::kKvAppend && ep.seg_cols == N && !ep.relu &&
+                       !ep.residual && N == 3 * fused->n_heads * fused->head_dim && fused->head_dim % 8 == 0;
+  if (pl.splits > 1) {
+    p.partial = (float*)workspace;
+  } else if (want_kv && (pl.variant == 2 || pl.variant == 4)) {
+    // unsplit (decode-sized tiles only): the tile kernel's own epilogue scatters K and V into the cache
+    p.ctx_lens = fused->ctx_lens; p.block_tables = fused->block_tables; p.max_blocks = fused->max_blocks;
+    p.k_cache = (uint16_t*)fused->k_cache; p.v_cache = (uint16_t*)fused->v_cache;
+    p.n_heads = fused->n_heads; p.head_dim = fused->head_dim;
+    if (fused_done) *fused_done = true;
   }
-  switch (variant) {
-    case 3: return launch_dl<256, 256, 2, 2, 2>(p, stream);
-    case 2: return launch_dl<128, 128, 2, 2, 3>(p, stream);
-    default: return launch_dl<256, 160, 4, 1, 3>(p, stream);
+  hipError_t e;
+  switch (pl.variant) {
+    case 4: e = launch_dl<64, 128, 1, 4, 3, true>(p, pl.splits, stream); break;
+    case 3: e = launch_dl<256, 256, 2, 2, 2, false>(p, pl.splits, stream); break;
+    case 2: e = launch_dl<128, 128, 2, 2, 3, true>(p, pl.splits, stream); break;
+    default: e = launch_dl<256, 160, 4, 1, 3, false>(p, pl.splits, stream); break;
   }
+  if (e != hipSuccess) return e;
+  if (pl.splits > 1) e = launch_splitk_reduce(p.partial, pl.splits, M, N, ep, fused, fused_done, stream);
+  return e;
 }
 
 }  // namespace ds

@@ -570,6 +570,41 @@ hipError_t launch_skinny_argmax(const void* X, const void* W, int M, int N, int 
   return launch_argmax_merge(p.amax_val, p.amax_idx, blocks, M, next_token, best_logit, stream);
 }
 
+// Second pass of any split-K product: partial [splits][M][N] fp32 -> epilogue, optionally with the
+// LayerNorm or KV-append work folded in (reported through *fused_done).
+hipError_t launch_splitk_reduce(const float* partial, int splits, int M, int N, const Epilogue& ep,
+                                const SkinnyFused* fused, bool* fused_done, hipStream_t stream) {
+  if (fused_done) *fused_done = false;
+  if (N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0) return hipErrorInvalidValue;
+  SkinnyParams p;
+  p.X = nullptr;
+  p.W = nullptr;
+  p.bias = (const uint16_t*)ep.bias;
+  p.residual = (const uint16_t*)ep.residual;
+  for (int i = 0; i < 3; ++i) p.out[i] = (uint16_t*)ep.out[i];
+  p.seg_cols = ep.seg_cols;
+  p.M = M; p.N = N; p.K = 0;
+  p.relu = ep.relu;
+  p.partial = const_cast<float*>(partial);
+  const long items = (long)M * (N / 8);
+  const unsigned blocks = (unsigned)((items + 255) / 256);
+  if (fused && fused->kind == SkinnyFused::kLayerNorm && ep.seg_cols == N && N <= 256 * 8 * kRedLnMaxChunks) {
+    hipLaunchKernelGGL(skinny_reduce_ln_kernel, dim3(M), dim3(256), 0, stream, p, splits,
+                       (const uint16_t*)fused->ln_gamma, (const uint16_t*)fused->ln_beta, fused->ln_eps,
+                       (uint16_t*)fused->ln_out);
+    if (fused_done) *fused_done = true;
+  } else if (fused && fused->kind == SkinnyFused::kKvAppend && ep.seg_cols == N && !ep.relu && !ep.residual &&
+             N == 3 * fused->n_heads * fused->head_dim) {
+    hipLaunchKernelGGL(skinny_reduce_kv_kernel, dim3(blocks), dim3(256), 0, stream, p, splits, fused->ctx_lens,
+                       fused->block_tables, fused->max_blocks, (uint16_t*)fused->k_cache,
+                       (uint16_t*)fused->v_cache, fused->n_heads, fused->head_dim);
+    if (fused_done) *fused_done = true;
+  } else {
+    hipLaunchKernelGGL(skinny_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p, splits);
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
                               void* workspace, hipStream_t stream, const SkinnyFused* fused, bool* fused_done) {
   if (fused_done) *fused_done = false;
@@ -591,25 +626,7 @@ hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K,
   if (pl.splits > 1 && workspace == nullptr) return hipErrorInvalidValue;
   hipError_t e = dispatch_skinny(p, pl, stream);
   if (e != hipSuccess) return e;
-  if (pl.splits > 1) {
-    const long items = (long)M * (N / 8);
-    const unsigned blocks = (unsigned)((items + 255) / 256);
-    if (fused && fused->kind == SkinnyFused::kLayerNorm && ep.seg_cols == N && N <= 256 * 8 * kRedLnMaxChunks) {
-      hipLaunchKernelGGL(skinny_reduce_ln_kernel, dim3(M), dim3(256), 0, stream, p, pl.splits,
-                         (const uint16_t*)fused->ln_gamma, (const uint16_t*)fused->ln_beta, fused->ln_eps,
-                         (uint16_t*)fused->ln_out);
-      if (fused_done) *fused_done = true;
-    } else if (fused && fused->kind == SkinnyFused::kKvAppend && ep.seg_cols == N && !ep.relu && !ep.residual &&
-               N == 3 * fused->n_heads * fused->head_dim) {
-      hipLaunchKernelGGL(skinny_reduce_kv_kernel, dim3(blocks), dim3(256), 0, stream, p, pl.splits,
-                         fused->ctx_lens, fused->block_tables, fused->max_blocks, (uint16_t*)fused->k_cache,
-                         (uint16_t*)fused->v_cache, fused->n_heads, fused->head_dim);
-      if (fused_done) *fused_done = true;
-    } else {
-      hipLaunchKernelGGL(skinny_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p, pl.splits);
-    }
-    e = hipGetLastError();
-  }
+  if (pl.splits > 1) e = launch_splitk_reduce(p.partial, pl.splits, M, N, ep, fused, fused_done, stream);
   return e;
 }
 

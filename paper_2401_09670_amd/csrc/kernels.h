@@ -25,9 +25,16 @@ struct Epilogue {
   int seg_cols = 0;  // N / number of segments; row stride of each out buffer
 };
 
-// Y[M,N] = X[M,K] W[N,K]^T (+ epilogue): MFMA tile kernel for large M (prefill).
+struct SkinnyFused;
+
+// Y[M,N] = X[M,K] W[N,K]^T (+ epilogue) on the MFMA tile kernel, any M.  Where the tiles alone
+// would not fill the chip (decode-sized M, narrow N) the K axis is split over workgroups: fp32
+// partials in `workspace` (gemm_workspace_bytes) and a second pass that also carries the epilogue.
+// `fused` asks for extra work (see SkinnyFused); *fused_done tells whether it was carried out.
+size_t gemm_workspace_bytes(int M, int N, int K);
 hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
-                       hipStream_t stream);
+                       hipStream_t stream, void* workspace = nullptr, const SkinnyFused* fused = nullptr,
+                       bool* fused_done = nullptr);
 
 // Work that the decode GEMM's split-K reduction can absorb (saves a launch each):
 //  kLayerNorm: after out = act(..) + residual is written, also write ln_out = LN(out) (row-wise).
@@ -46,6 +53,9 @@ struct SkinnyFused {
   void* v_cache = nullptr;
   int n_heads = 0, head_dim = 0;
 };
+
+hipError_t launch_splitk_reduce(const float* partial, int splits, int M, int N, const Epilogue& ep,
+                                const SkinnyFused* fused, bool* fused_done, hipStream_t stream);
 
 // Same contraction for M <= 256 (decode): weights are streamed once from HBM.
 // `*fused_done` tells whether the requested fused work was carried out (it needs the split-K

@@ -205,3 +205,21 @@ def test_tensor_parallel_shard_shapes(gpu, name, hidden, n_heads, ffn):
     _migrate_and_check(ctx, shape, k_out, v_out, lens, seed)
     ctxs = synth.uniform_lengths(48, 1, 900, seed, stream=3)
     _decode_and_check(shape, lw, w32, ctxs, seed, [0, int(np.argmax(ctxs)), int(np.argmin(ctxs))], steps=2)
+
+
+@pytest.mark.parametrize("hidden,n_heads,ffn,B", [
+    (1024, 8, 4096, 200),     # QKV / FFN-in split over K on the tile kernel: K,V arrive through the reduce pass
+    (256, 2, 1024, 150),      # too few k-tiles to split: K,V scattered by the tile kernel's own epilogue
+    (2048, 16, 8192, 129),    # just past the row count where the weight-streaming kernel hands over
+])
+def test_decode_step_wide_batches(gpu, hidden, n_heads, ffn, B):
+    """Decode batches of more than 128 rows take the MFMA tile kernel (with or without split-K); every
+    fusion of the step (KV append, LayerNorm-2) must give the same layer as the oracle's."""
+    shape = synth.ModelShape(hidden=hidden, n_heads=n_heads, head_dim=128, ffn=ffn)
+    seed = 31337 + hidden
+    lw, wdev = gu.dev_layer_weights(shape, seed)
+    w64 = orc.weights_from_bits(gu.host_weights(wdev), np.float64)
+    ctxs = synth.uniform_lengths(B, 1, 200, seed, stream=5)
+    sample = sorted(set([0, B - 1, int(np.argmax(ctxs)), int(np.argmin(ctxs))] +
+                        [int(i) for i in np.random.default_rng(seed).integers(0, B, size=12)]))
+    _decode_and_check(shape, lw, w64, ctxs, seed, sample, steps=3)

@@ -88,6 +88,9 @@ def _linear_case(ctx, rows, in_f, out_f, bias, relu, residual, seed):
     (2048, 512, 5120, True, False, True),     # the 256x160 tile with exact quantisation
     (700, 320, 160, False, False, True),      # K = 5 k-tiles, one column tile
     (1111, 192, 2048, False, True, False),
+    (200, 5120, 5120, True, False, True),     # decode-sized rows on the tile kernel: split over K + reduce pass
+    (129, 2048, 256, True, True, False),      # very few tiles: many splits
+    (256, 4096, 1032, False, False, False),   # split-K with a ragged last column tile
 ])
 def test_linear_tile_path(gpu, rows, in_f, out_f, bias, relu, residual):
     ctx = gu.make_ctx(synth.TINY)
