@@ -247,7 +247,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
     //                  fetching the first-half fragments of tile kt+1
     // With two buffers the same schedule holds with one k-tile of flight time: at the barrier tile
     // kt+1 (requested during the second half of tile kt-1) must have landed completely.
-    static_assert(STAGES == 2 || STAGES == 3, "the schedule is written for 2 or 3 buffers");
+    static_assert(STAGES == 2 || STAGES == 3, "ring of 2 or 3 buffers");
 #pragma unroll
     for (int st = 0; st < STAGES; ++st) issue(st, st);
     wait_vmcnt<(STAGES - 1) * LPS>();
