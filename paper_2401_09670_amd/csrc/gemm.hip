@@ -29,7 +29,7 @@ struct GemmParams {
   int M, N, K;
   int relu;
   int tiles_m, tiles_n;
-  // Split-K (gridDim.y > 1): split s multiplies k-tiles [KT s / S, KT (s+1) / S) and stores its fp32
+  // Split-K (gridDim.y = S > 1): split s multiplies k-tiles s, s + S, ... and stores its fp32
   // accumulators to partial[s][M][N]; the epilogue then belongs to whoever adds the partials.
   float* partial;
   // Decode QKV projection (N = 3 n_heads head_dim): with k_cache set, the K and V thirds of row m go to
@@ -98,9 +98,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   const int m0 = (tile % p.tiles_m) * BM;
   const int n0 = (tile / p.tiles_m) * BN;
   const int K = p.K;
-  const int kt_first = EPI == kEpiPartial ? (int)((long)(K / kBK) * blockIdx.y / gridDim.y) : 0;
-  const int KT = EPI == kEpiPartial ? (int)((long)(K / kBK) * (blockIdx.y + 1) / gridDim.y) - kt_first  // >= 1
-                                    : K / kBK;
+  // Split-K deals the k-tiles round-robin (split s takes tiles s, s + S, ...), as the weight-streaming
+  // kernel does: the splits of one output tile read neighbouring 128-byte pieces of the same rows at
+  // about the same time.  (Measured no different from contiguous K ranges per split.)
+  const int kt_step = EPI == kEpiPartial ? (int)gridDim.y : 1;
+  const int kt_first = EPI == kEpiPartial ? (int)blockIdx.y : 0;
+  const int KT = (K / kBK - kt_first + kt_step - 1) / kt_step;  // >= 1: splits <= K / 64
 
   // per-lane source offsets (elements) of this wave's loads; load j covers rows 8*(4j+wave) .. +7
   const int lrow = lane >> 3;
@@ -121,7 +124,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   // harmless re-load into a buffer nobody reads again): this keeps the main loop free of branches, so
   // the loads can be interleaved with MFMAs by the scheduler.
   auto issue_one = [&](int stage, int kt_load, int j) {   // j in [0, LPS): X loads first, then W loads
-    const int kofs = (kt_first + min(kt_load, KT - 1)) * kBK;
+    const int kofs = (kt_first + min(kt_load, KT - 1) * kt_step) * kBK;
     uint16_t* xb = lds + stage * STAGE_ELEMS + wave_s * 512;     // 512 elements = 1 KB per wave-load
     if (j < XL) {
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.X + kofs + xoff[j]),
