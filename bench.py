@@ -32,6 +32,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--small", action="store_true", help="tiny config (debug only; not a valid bench line)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the side measurements (keeps a profiler's per-kernel averages to the workload itself)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device copy (known traffic) for calibrating rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters")
@@ -217,7 +219,7 @@ def main():
 
     # ---------------- extra: the KV hand-off at a size that does not fit the 256 MB last-level cache ----------------
     extras = {}
-    if not args.small:
+    if not args.small and not args.no_extras:
         Bm, Lm = 8, 2048                      # 16384 tokens of this layer's K and V: 2 x 168 MB read + written
         tm_ = Bm * Lm
         ks = torch.empty(tm_, h, dtype=torch.bfloat16, device=dev).normal_()

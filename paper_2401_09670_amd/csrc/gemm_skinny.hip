@@ -305,32 +305,46 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkinnyParams p
 // The same reduction, one workgroup per output row, followed by LayerNorm of that row: writes
 // out[0][m,:] = act(sum + bias) + residual (bf16) and ln_out[m,:] = LN(out[m,:]) (statistics in
 // fp32 over the bf16-rounded row, exactly what the stand-alone LayerNorm kernel would see).
-constexpr int kRedLnMaxChunks = 8;  // 8 chunks x 8 columns x 256 threads = 16384 columns
-__global__ __launch_bounds__(256) void skinny_reduce_ln_kernel(const SkinnyParams p, int n_splits,
-                                                               const uint16_t* __restrict__ gamma,
-                                                               const uint16_t* __restrict__ beta, float eps,
-                                                               uint16_t* __restrict__ ln_out) {
-  __shared__ float red[4];
+// 1024 threads per row so that a 5120-wide row is one 8-column piece per thread and all partial loads of a
+// row are in flight together (the kernel is pure latency: 64 rows, a few hundred KB each).
+constexpr int kRedLnThreads = 1024;
+constexpr int kRedLnMaxChunks = 2;  // 2 pieces x 8 columns x 1024 threads = 16384 columns
+template <int NCH>
+__global__ __launch_bounds__(kRedLnThreads) void skinny_reduce_ln_kernel(const SkinnyParams p, int n_splits,
+                                                                         const uint16_t* __restrict__ gamma,
+                                                                         const uint16_t* __restrict__ beta, float eps,
+                                                                         uint16_t* __restrict__ ln_out) {
+  __shared__ float red[kRedLnThreads / 64];
   const int m = blockIdx.x;
   const int nchunk = p.N >> 3;
-  float vals[kRedLnMaxChunks][8];
+  float vals[NCH][8];
   float sum = 0.f;
 #pragma unroll
-  for (int i = 0; i < kRedLnMaxChunks; ++i) {
-    const int c = threadIdx.x + i * 256;
+  for (int i = 0; i < NCH; ++i) {
+    const int c = threadIdx.x + i * kRedLnThreads;
     if (c < nchunk) {
       const int n = c * 8;
       float v[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) v[j] = 0.f;
-      for (int s = 0; s < n_splits; ++s) {
-        const float* src = p.partial + ((size_t)s * p.M + m) * p.N + n;
-        const floatx4 a = *reinterpret_cast<const floatx4*>(src);
-        const floatx4 b = *reinterpret_cast<const floatx4*>(src + 4);
+      // four splits' loads are issued together, then added in split order
+      for (int s0 = 0; s0 < n_splits; s0 += 4) {
+        floatx4 a[4], b[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          v[j] += a[j];
-          v[4 + j] += b[j];
+        for (int u = 0; u < 4; ++u) {
+          const float* src = p.partial + ((size_t)min(s0 + u, n_splits - 1) * p.M + m) * p.N + n;
+          a[u] = *reinterpret_cast<const floatx4*>(src);
+          b[u] = *reinterpret_cast<const floatx4*>(src + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (s0 + u < n_splits) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              v[j] += a[u][j];
+              v[4 + j] += b[u][j];
+            }
+          }
         }
       }
       if (p.bias) {
@@ -369,13 +383,16 @@ __global__ __launch_bounds__(256) void skinny_reduce_ln_kernel(const SkinnyParam
     __syncthreads();
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    return red[0] + red[1] + red[2] + red[3];
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < kRedLnThreads / 64; ++w) t += red[w];
+    return t;
   };
   const float mean = block_sum(sum) / (float)p.N;
   float sq = 0.f;
 #pragma unroll
-  for (int i = 0; i < kRedLnMaxChunks; ++i) {
-    const int c = threadIdx.x + i * 256;
+  for (int i = 0; i < NCH; ++i) {
+    const int c = threadIdx.x + i * kRedLnThreads;
     if (c < nchunk) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -386,8 +403,8 @@ __global__ __launch_bounds__(256) void skinny_reduce_ln_kernel(const SkinnyParam
   }
   const float rstd = rsqrtf(block_sum(sq) / (float)p.N + eps);
 #pragma unroll
-  for (int i = 0; i < kRedLnMaxChunks; ++i) {
-    const int c = threadIdx.x + i * 256;
+  for (int i = 0; i < NCH; ++i) {
+    const int c = threadIdx.x + i * kRedLnThreads;
     if (c < nchunk) {
       const u32x4 g = ld16(gamma + c * 8);
       const u32x4 b = ld16(beta + c * 8);
@@ -588,10 +605,16 @@ hipError_t launch_splitk_reduce(const float* partial, int splits, int M, int N, 
   p.partial = const_cast<float*>(partial);
   const long items = (long)M * (N / 8);
   const unsigned blocks = (unsigned)((items + 255) / 256);
-  if (fused && fused->kind == SkinnyFused::kLayerNorm && ep.seg_cols == N && N <= 256 * 8 * kRedLnMaxChunks) {
-    hipLaunchKernelGGL(skinny_reduce_ln_kernel, dim3(M), dim3(256), 0, stream, p, splits,
-                       (const uint16_t*)fused->ln_gamma, (const uint16_t*)fused->ln_beta, fused->ln_eps,
-                       (uint16_t*)fused->ln_out);
+  if (fused && fused->kind == SkinnyFused::kLayerNorm && ep.seg_cols == N &&
+      N <= kRedLnThreads * 8 * kRedLnMaxChunks) {
+    if (N <= kRedLnThreads * 8)
+      hipLaunchKernelGGL(skinny_reduce_ln_kernel<1>, dim3(M), dim3(kRedLnThreads), 0, stream, p, splits,
+                         (const uint16_t*)fused->ln_gamma, (const uint16_t*)fused->ln_beta, fused->ln_eps,
+                         (uint16_t*)fused->ln_out);
+    else
+      hipLaunchKernelGGL(skinny_reduce_ln_kernel<2>, dim3(M), dim3(kRedLnThreads), 0, stream, p, splits,
+                         (const uint16_t*)fused->ln_gamma, (const uint16_t*)fused->ln_beta, fused->ln_eps,
+                         (uint16_t*)fused->ln_out);
     if (fused_done) *fused_done = true;
   } else if (fused && fused->kind == SkinnyFused::kKvAppend && ep.seg_cols == N && !ep.relu && !ep.residual &&
              N == 3 * fused->n_heads * fused->head_dim) {
