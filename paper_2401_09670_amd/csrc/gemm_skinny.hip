@@ -255,6 +255,32 @@ __global__ __launch_bounds__(kSkThreads) void skinny_gemm_kernel(const SkinnyPar
   }
 }
 
+// Sum of the split partials of 8 consecutive columns of row m, added in split order; the loads of four
+// splits are issued together (the reduce passes are latency-bound).
+__device__ __forceinline__ void sum_partials8(const SkinnyParams& p, int n_splits, int m, int n, float v[8]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = 0.f;
+  for (int s0 = 0; s0 < n_splits; s0 += 4) {
+    floatx4 a[4], b[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float* src = p.partial + ((size_t)min(s0 + u, n_splits - 1) * p.M + m) * p.N + n;
+      a[u] = *reinterpret_cast<const floatx4*>(src);
+      b[u] = *reinterpret_cast<const floatx4*>(src + 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (s0 + u < n_splits) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          v[j] += a[u][j];
+          v[4 + j] += b[u][j];
+        }
+      }
+    }
+  }
+}
+
 // Sum the split partials in split order, then bias / ReLU / residual, 8 columns per thread.
 __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkinnyParams p, int n_splits) {
   const int chunks_per_row = p.N >> 3;
@@ -263,18 +289,7 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkinnyParams p
   const int m = (int)(idx / chunks_per_row);
   const int n = (int)(idx % chunks_per_row) * 8;
   float v[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) v[j] = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const float* src = p.partial + ((size_t)s * p.M + m) * p.N + n;
-    const floatx4 a = *reinterpret_cast<const floatx4*>(src);
-    const floatx4 b = *reinterpret_cast<const floatx4*>(src + 4);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      v[j] += a[j];
-      v[4 + j] += b[j];
-    }
-  }
+  sum_partials8(p, n_splits, m, n, v);
   if (p.bias) {
     const u32x4 bb = ld16(p.bias + n);
 #pragma unroll
@@ -325,28 +340,7 @@ __global__ __launch_bounds__(kRedLnThreads) void skinny_reduce_ln_kernel(const S
     if (c < nchunk) {
       const int n = c * 8;
       float v[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) v[j] = 0.f;
-      // four splits' loads are issued together, then added in split order
-      for (int s0 = 0; s0 < n_splits; s0 += 4) {
-        floatx4 a[4], b[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const float* src = p.partial + ((size_t)min(s0 + u, n_splits - 1) * p.M + m) * p.N + n;
-          a[u] = *reinterpret_cast<const floatx4*>(src);
-          b[u] = *reinterpret_cast<const floatx4*>(src + 4);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (s0 + u < n_splits) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              v[j] += a[u][j];
-              v[4 + j] += b[u][j];
-            }
-          }
-        }
-      }
+      sum_partials8(p, n_splits, m, n, v);
       if (p.bias) {
         const u32x4 bb = ld16(p.bias + n);
 #pragma unroll
@@ -435,18 +429,7 @@ __global__ __launch_bounds__(256) void skinny_reduce_kv_kernel(const SkinnyParam
   const int m = (int)(idx / chunks_per_row);
   const int n = (int)(idx % chunks_per_row) * 8;
   float v[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) v[j] = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const float* src = p.partial + ((size_t)s * p.M + m) * p.N + n;
-    const floatx4 a = *reinterpret_cast<const floatx4*>(src);
-    const floatx4 b = *reinterpret_cast<const floatx4*>(src + 4);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      v[j] += a[j];
-      v[4 + j] += b[j];
-    }
-  }
+  sum_partials8(p, n_splits, m, n, v);
   if (p.bias) {
     const u32x4 bb = ld16(p.bias + n);
 #pragma unroll
