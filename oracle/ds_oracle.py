@@ -17,8 +17,11 @@ What it computes (numpy, float64 unless ``dtype`` says otherwise):
       f  = LN(x1; g2, b2)
       u  = relu(f W_1^T + b_1)                 (t,h) x (h,m)
       y  = x1 + u W_2^T + b_2                  (t,m) x (m,h)
-  Matrices are held ``[out, in]``; ``w_qkv`` rows are ``[Q|K|V]``, each third
-  ordered ``head*s + d``.
+  Matrices are held ``[out, in]``; ``w_qkv`` rows are ``[Q|K|V]``, each part
+  ordered ``head*s + d``.  The K and V parts may have fewer heads than Q
+  (grouped-query attention, named in Sec. 3.2): ``w_qkv`` is then
+  ``[(n + 2 n_kv) s, h]`` and query head j uses key/value head ``j // (n/n_kv)``;
+  n_kv is read off the matrix shape.
 * The decode step (App. A.3): the same layer for one new row per request whose
   attention runs over the request's cached keys/values plus its own.  Because
   the KV cache exists only to avoid recomputation (Sec. 2.1), the defining
@@ -84,11 +87,12 @@ def attention_probs(q_rows: np.ndarray, pos: np.ndarray, k: np.ndarray) -> np.nd
     keys ``0..pos[r]``; keys after ``pos[r]`` get weight exactly 0."""
     R, n, s = q_rows.shape
     l = k.shape[0]
+    g = n // k.shape[1]  # query heads per key/value head (1 = ordinary multi-head attention)
     pos = np.asarray(pos).reshape(R, 1)
     allowed = np.arange(l).reshape(1, l) <= pos
     p = np.zeros((n, R, l), dtype=q_rows.dtype)
     for j in range(n):
-        e = (q_rows[:, j, :] @ k[:, j, :].T) / math.sqrt(s)
+        e = (q_rows[:, j, :] @ k[:, j // g, :].T) / math.sqrt(s)
         e = np.where(allowed, e, -np.inf)
         e = e - e.max(axis=1, keepdims=True)
         w = np.exp(e)
@@ -101,21 +105,30 @@ def attention_rows(q_rows: np.ndarray, pos: np.ndarray, k: np.ndarray, v: np.nda
 
     ``q_rows[R,n,s]`` are queries at positions ``pos[R]`` of a request whose
     keys/values are ``k, v[l,n,s]``.  Prefill uses all rows (pos = 0..l-1),
-    a decode step uses one row (pos = l-1)."""
+    a decode step uses one row (pos = l-1).
+
+    With fewer key/value heads than query heads (``k, v[l,n_kv,s]``, n_kv
+    dividing n: grouped-query attention, which Sec. 3.2 names as a way to
+    shrink the KV cache) query head j reads key/value head ``j // (n / n_kv)``."""
     p = attention_probs(q_rows, pos, k)
     R, n, s = q_rows.shape
+    g = n // v.shape[1]
     o = np.empty((R, n, s), dtype=q_rows.dtype)
     for j in range(n):
-        o[:, j, :] = p[j] @ v[:, j, :]
+        o[:, j, :] = p[j] @ v[:, j // g, :]
     return o
 
 
 def _split_qkv(qkv: np.ndarray, n: int, s: int):
+    """Columns are [Q: n heads | K: n_kv heads | V: n_kv heads]; n_kv follows from the width."""
     h = n * s
     rows = qkv.shape[0]
+    n_kv = (qkv.shape[1] // s - n) // 2
+    assert (n + 2 * n_kv) * s == qkv.shape[1] and n % n_kv == 0
+    hk = n_kv * s
     q = qkv[:, 0:h].reshape(rows, n, s)
-    k = qkv[:, h:2 * h].reshape(rows, n, s)
-    v = qkv[:, 2 * h:3 * h].reshape(rows, n, s)
+    k = qkv[:, h:h + hk].reshape(rows, n_kv, s)
+    v = qkv[:, h + hk:h + 2 * hk].reshape(rows, n_kv, s)
     return q, k, v
 
 
@@ -162,8 +175,9 @@ def layer_prefill_rows(w: Dict[str, np.ndarray], x_seq: np.ndarray, rows: Sequen
     a = layernorm(x_seq, w["ln1_g"], w["ln1_b"], eps)
     bq = w.get("b_qkv")
     kv = linear(a, w["w_qkv"][h:], None if bq is None else bq[h:])
-    k = kv[:, :h].reshape(l, n_heads, s)
-    v = kv[:, h:].reshape(l, n_heads, s)
+    hk = kv.shape[1] // 2                      # n_kv * s
+    k = kv[:, :hk].reshape(l, hk // s, s)
+    v = kv[:, hk:].reshape(l, hk // s, s)
     q = linear(a[rows], w["w_qkv"][:h], None if bq is None else bq[:h]).reshape(len(rows), n_heads, s)
     o = attention_rows(q, rows, k, v)
     y = _post_attention(w, x_seq[rows], o, eps)

@@ -33,9 +33,20 @@ class ModelShape:
     block_size: int = 16   # tokens per KV page
     n_layers: int = 1
     ln_eps: float = 1e-5
+    n_kv_heads: int = 0    # key/value heads; 0 = as many as query heads (multi-head attention)
 
     def __post_init__(self):
         assert self.hidden == self.n_heads * self.head_dim
+        assert self.n_heads % self.kv_heads == 0
+
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads or self.n_heads
+
+    @property
+    def qkv_width(self) -> int:
+        """Output features of the QKV projection: (n + 2 n_kv) s."""
+        return (self.n_heads + 2 * self.kv_heads) * self.head_dim
 
 
 TINY = ModelShape(hidden=256, n_heads=4, head_dim=64, ffn=1024)
@@ -96,8 +107,8 @@ def make_layer_weights(shape: ModelShape, seed: int, layer: int = 0) -> Dict[str
     w = {}
     w["ln1_g"] = _normal_bf16(rng, (h,), 1.0, 0.02)
     w["ln1_b"] = _normal_bf16(rng, (h,), 0.0, 0.02)
-    w["w_qkv"] = _normal_bf16(rng, (3 * h, h), 0.0, 0.02)
-    w["b_qkv"] = _normal_bf16(rng, (3 * h,), 0.0, 0.02)
+    w["w_qkv"] = _normal_bf16(rng, (shape.qkv_width, h), 0.0, 0.02)
+    w["b_qkv"] = _normal_bf16(rng, (shape.qkv_width,), 0.0, 0.02)
     w["w_o"] = _normal_bf16(rng, (h, h), 0.0, 0.02)
     w["b_o"] = _normal_bf16(rng, (h,), 0.0, 0.02)
     w["ln2_g"] = _normal_bf16(rng, (h,), 1.0, 0.02)
@@ -118,8 +129,8 @@ def make_activations(rows: int, hidden: int, seed: int, stream: int = 0) -> np.n
 def make_kv_fill(tokens: int, shape: ModelShape, seed: int, stream: int = 0):
     """``[tokens, n, s]`` N(0, 1) K and V rows (bf16 bits) for pre-filling a cache."""
     rng = np.random.Generator(np.random.Philox(key=[seed, 3000 + stream]))
-    k = _normal_bf16(rng, (tokens, shape.n_heads, shape.head_dim), 0.0, 1.0)
-    v = _normal_bf16(rng, (tokens, shape.n_heads, shape.head_dim), 0.0, 1.0)
+    k = _normal_bf16(rng, (tokens, shape.kv_heads, shape.head_dim), 0.0, 1.0)
+    v = _normal_bf16(rng, (tokens, shape.kv_heads, shape.head_dim), 0.0, 1.0)
     return k, v
 
 

@@ -425,3 +425,61 @@ def test_greedy_brute_force_and_ties():
         want.append(best)
     got = orc.greedy(logits)
     assert got.tolist() == want and got[2] == 17 and got[3] == 0 and got[4] == 299
+
+
+# ---------------------------------------------------------------------------------------------
+# Grouped-query attention (fewer key/value heads than query heads; Sec. 3.2 names it)
+# ---------------------------------------------------------------------------------------------
+def _repeat_kv_weights(w, n, n_kv, s):
+    """The multi-head layer that a grouped-query layer is by definition equal to: every key/value
+    head's projection rows copied to each query head of its group."""
+    h, hk, g = n * s, n_kv * s, n // n_kv
+    wq, wk, wv = w["w_qkv"][:h], w["w_qkv"][h:h + hk], w["w_qkv"][h + hk:]
+    bq, bk, bv = w["b_qkv"][:h], w["b_qkv"][h:h + hk], w["b_qkv"][h + hk:]
+    rep_rows = lambda m: np.repeat(m.reshape(n_kv, s, -1), g, axis=0).reshape(n * s, -1)
+    rep_vec = lambda v: np.repeat(v.reshape(n_kv, s), g, axis=0).reshape(n * s)
+    out = dict(w)
+    out["w_qkv"] = np.concatenate([wq, rep_rows(wk), rep_rows(wv)], axis=0)
+    out["b_qkv"] = np.concatenate([bq, rep_vec(bk), rep_vec(bv)])
+    return out
+
+
+def test_gqa_layer_equals_multi_head_layer_with_repeated_kv_heads():
+    shape = synth.ModelShape(hidden=64, n_heads=8, head_dim=8, ffn=96, n_kv_heads=2)
+    w = orc.weights_from_bits(synth.make_layer_weights(shape, 5))
+    assert w["w_qkv"].shape == ((8 + 2 * 2) * 8, 64)
+    lens = [5, 1, 9]
+    x = orc.from_bf16_bits(synth.make_activations(sum(lens), 64, 5))
+    y, k, v = orc.layer_prefill(w, x, lens, 8)
+    assert k.shape == (15, 2, 8) and v.shape == (15, 2, 8)
+    w_mha = _repeat_kv_weights(w, 8, 2, 8)
+    y2, k2, v2 = orc.layer_prefill(w_mha, x, lens, 8)
+    assert np.allclose(y, y2, rtol=0, atol=1e-13)
+    assert np.array_equal(k2[:, ::4], k) and np.array_equal(k2[:, 3::4], k)   # group of 4 shares one head
+    # row-sampled form and the decode forms agree with it as well
+    yr, kr, vr = orc.layer_prefill_rows(w, x[:5], [0, 4], 8)
+    assert np.allclose(yr, y[[0, 4]], atol=1e-13) and np.allclose(kr, k[:5], atol=1e-13) and kr.shape == (5, 2, 8)
+    hist, new = x[6:14], x[14]
+    want = orc.layer_decode_recompute(w_mha, hist, new, 8)
+    assert np.allclose(orc.layer_decode_recompute(w, hist, new, 8), want, atol=1e-13)
+    bt, nblk = synth.make_block_tables([9], 16, 3)
+    kc = np.zeros((nblk, 2, 16, 8)); vc = np.zeros_like(kc)
+    orc.kv_migrate(k[6:14], v[6:14], [8], bt, kc, vc)
+    got = orc.layer_decode_cached(w, new.reshape(1, -1), [8], bt, kc, vc, 8)
+    assert np.allclose(got[0], want, atol=1e-13)
+
+
+def test_gqa_attention_against_torch_sdpa_with_repeated_heads():
+    rng = np.random.default_rng(21)
+    l, n, n_kv, s = 11, 6, 3, 16
+    q, k, v = rng.normal(size=(l, n, s)), rng.normal(size=(l, n_kv, s)), rng.normal(size=(l, n_kv, s))
+    got = orc.attention_rows(q, np.arange(l), k, v)
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(np.repeat(k, n // n_kv, axis=1)).permute(1, 0, 2)[None]
+    tv = torch.from_numpy(np.repeat(v, n // n_kv, axis=1)).permute(1, 0, 2)[None]
+    want = F.scaled_dot_product_attention(tq, tk, tv, is_causal=True)[0].permute(1, 0, 2).numpy()
+    assert np.allclose(got, want, atol=1e-12)
+    # one key/value head for all query heads (multi-query attention) is the extreme case
+    got1 = orc.attention_rows(q, np.arange(l), k[:, :1], v[:, :1])
+    for j in range(n):
+        assert np.allclose(got1[:, j], orc.attention_rows(q[:, j:j + 1], np.arange(l), k[:, :1], v[:, :1])[:, 0])
