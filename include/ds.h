@@ -48,7 +48,12 @@ typedef enum {
 } ds_status;
 
 /* Layer dimensions.  Supported: head_dim in {64,128}; hidden = n_heads*head_dim;
- * hidden and ffn multiples of 64; block_size = 16. */
+ * hidden and ffn multiples of 64; block_size = 16.  n_kv_heads (0 = n_heads) is the
+ * number of key/value heads n_kv; with n_kv < n (n % n_kv == 0: grouped-query
+ * attention, which Sec. 3.2 names as a way to shrink the KV cache) query head j
+ * uses key/value head j / (n/n_kv), and wherever this header writes "n" for a K or
+ * V tensor (k_out, v_out, the paged caches) n_kv is meant; w_qkv is
+ * [(n + 2 n_kv) s, h] with rows [Q | K | V]. */
 typedef struct {
   int32_t hidden;     /* h */
   int32_t n_heads;    /* n */
@@ -56,6 +61,7 @@ typedef struct {
   int32_t ffn;        /* m */
   int32_t block_size; /* tokens per KV page */
   float ln_eps;       /* LayerNorm epsilon (biased variance, fp32 statistics) */
+  int32_t n_kv_heads; /* n_kv; 0 means n_heads */
 } ds_model_cfg;
 
 /* One layer's parameters: device pointers to bf16.  Bias pointers may be NULL

@@ -36,7 +36,8 @@ class DsError(RuntimeError):
 
 class ModelCfg(ctypes.Structure):
     _fields_ = [("hidden", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
-                ("ffn", ctypes.c_int32), ("block_size", ctypes.c_int32), ("ln_eps", ctypes.c_float)]
+                ("ffn", ctypes.c_int32), ("block_size", ctypes.c_int32), ("ln_eps", ctypes.c_float),
+                ("n_kv_heads", ctypes.c_int32)]
 
 
 class LayerWeights(ctypes.Structure):
@@ -120,9 +121,9 @@ class Context:
     """``ds_ctx`` for one layer shape; methods mirror the C entry points."""
 
     def __init__(self, hidden: int, n_heads: int, head_dim: int, ffn: int, block_size: int = 16,
-                 ln_eps: float = 1e-5):
+                 ln_eps: float = 1e-5, n_kv_heads: int = 0):
         self.lib = load_library()
-        self.cfg = ModelCfg(hidden, n_heads, head_dim, ffn, block_size, ln_eps)
+        self.cfg = ModelCfg(hidden, n_heads, head_dim, ffn, block_size, ln_eps, n_kv_heads)
         self.handle = ctypes.c_void_p()
         st = self.lib.ds_create(ctypes.byref(self.cfg), ctypes.byref(self.handle))
         if st != DS_OK:

@@ -37,7 +37,7 @@ template <int HD>
 __global__ __launch_bounds__(kDecThreads) void decode_attention_kernel(
     const uint16_t* __restrict__ q, int q_stride, const int32_t* __restrict__ kv_lens, int kv_len_add,
     const int32_t* __restrict__ block_tables, int max_blocks, const uint16_t* __restrict__ k_cache,
-    const uint16_t* __restrict__ v_cache, int n_heads, int pages_per_split, float scale_log2e,
+    const uint16_t* __restrict__ v_cache, int n_heads, int n_kv_heads, int pages_per_split, float scale_log2e,
     uint16_t* __restrict__ o, float* __restrict__ partial) {
   constexpr int LPT = HD / 8;          // lanes per token row
   constexpr int TPL = 64 / LPT;        // tokens per load instruction
@@ -45,7 +45,13 @@ __global__ __launch_bounds__(kDecThreads) void decode_attention_kernel(
   __shared__ float sm_m[kDecWaves], sm_l[kDecWaves];
   __shared__ float sm_acc[kDecWaves][HD];
 
-  const int head = blockIdx.x, seq = blockIdx.y, split = blockIdx.z;
+  // Query heads that share a key/value head are n_kv_heads apart in launch order: with n_kv_heads a
+  // multiple of 8 they land on the same chip partition at about the same time, so the group's K/V
+  // pages come out of that partition's L2 after the first reader.  (Plain identity for n_kv = n.)
+  const int kv_group = n_heads / n_kv_heads;
+  const int kv_head = blockIdx.x % n_kv_heads;
+  const int head = kv_head * kv_group + blockIdx.x / n_kv_heads;
+  const int seq = blockIdx.y, split = blockIdx.z;
   const int n_splits = gridDim.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tg = lane / LPT, dc = lane % LPT;
@@ -69,7 +75,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_attention_kernel(
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const size_t lane_off = (size_t)tg * HD + dc * 8;
   auto fetch = [&](int blk, u32x4* kd, u32x4* vd) {
-    const size_t base = ((size_t)blk * n_heads + head) * page_elems + lane_off;
+    const size_t base = ((size_t)blk * n_kv_heads + kv_head) * page_elems + lane_off;
 #pragma unroll
     for (int j = 0; j < NL; ++j) kd[j] = ld16(k_cache + base + (size_t)j * TPL * HD);
 #pragma unroll
@@ -209,9 +215,10 @@ size_t decode_attention_workspace_bytes(int B, int n_heads, int head_dim, int ma
 
 hipError_t launch_decode_attention(const void* q, int q_stride, const int32_t* kv_lens, int kv_len_add,
                                    const int32_t* block_tables, int B, int max_blocks, int max_kv_len,
-                                   const void* k_cache, const void* v_cache, int n_heads, int head_dim,
-                                   void* o, void* workspace, hipStream_t stream) {
+                                   const void* k_cache, const void* v_cache, int n_heads, int n_kv_heads,
+                                   int head_dim, void* o, void* workspace, hipStream_t stream) {
   if (B <= 0) return hipSuccess;
+  if (n_kv_heads <= 0 || n_heads % n_kv_heads != 0) return hipErrorInvalidValue;
   if (B > 65535) return hipErrorInvalidValue;
   const int splits = decode_attention_splits(B, n_heads, max_kv_len);
   const int pages = (max_kv_len + kDecPage - 1) / kDecPage;
@@ -221,14 +228,14 @@ hipError_t launch_decode_attention(const void* q, int q_stride, const int32_t* k
   if (head_dim == 128) {
     hipLaunchKernelGGL(decode_attention_kernel<128>, grid, dim3(kDecThreads), 0, stream, (const uint16_t*)q,
                        q_stride, kv_lens, kv_len_add, block_tables, max_blocks, (const uint16_t*)k_cache,
-                       (const uint16_t*)v_cache, n_heads, pps, scale_log2e, (uint16_t*)o, (float*)workspace);
+                       (const uint16_t*)v_cache, n_heads, n_kv_heads, pps, scale_log2e, (uint16_t*)o, (float*)workspace);
     if (splits > 1)
       hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(B * n_heads), dim3(128), 0, stream,
                          (const float*)workspace, splits, scale_log2e, (uint16_t*)o);
   } else if (head_dim == 64) {
     hipLaunchKernelGGL(decode_attention_kernel<64>, grid, dim3(kDecThreads), 0, stream, (const uint16_t*)q,
                        q_stride, kv_lens, kv_len_add, block_tables, max_blocks, (const uint16_t*)k_cache,
-                       (const uint16_t*)v_cache, n_heads, pps, scale_log2e, (uint16_t*)o, (float*)workspace);
+                       (const uint16_t*)v_cache, n_heads, n_kv_heads, pps, scale_log2e, (uint16_t*)o, (float*)workspace);
     if (splits > 1)
       hipLaunchKernelGGL(decode_combine_kernel<64>, dim3(B * n_heads), dim3(64), 0, stream,
                          (const float*)workspace, splits, scale_log2e, (uint16_t*)o);

@@ -23,7 +23,8 @@ constexpr int kVtStride = kAttKV + 4;  // elements per V^T row (136 B): 8-byte r
 template <int HD>
 __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))) void prefill_attention_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const int32_t* __restrict__ cu_seqlens, uint16_t* __restrict__ o, int n_heads, float scale_log2e,
+    const int32_t* __restrict__ cu_seqlens, uint16_t* __restrict__ o, int n_heads, int kv_group,
+    float scale_log2e,
     int n_pairs, int pairs_per_xcd, int n_qt, int qt_fast) {
   constexpr int KS = HD + 8;        // K tile row stride in elements
   constexpr int DSTEPS = HD / 16;   // MFMA k-steps over the head dimension
@@ -52,9 +53,10 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int hl = lane >> 5, lq = lane & 31;
-  const size_t h = (size_t)n_heads * HD;
-  const uint16_t* kbase = k + (size_t)start * h + (size_t)head * HD;
-  const uint16_t* vbase = v + (size_t)start * h + (size_t)head * HD;
+  const size_t h = (size_t)n_heads * HD;                // q, o row length
+  const size_t hk = (size_t)(n_heads / kv_group) * HD;  // k, v row length: kv_group query heads share a key/value head
+  const uint16_t* kbase = k + (size_t)start * hk + (size_t)(head / kv_group) * HD;
+  const uint16_t* vbase = v + (size_t)start * hk + (size_t)(head / kv_group) * HD;
 
   const int qw0 = q0 + wave * 32;  // first query of this wave
   const int my_q = qw0 + lq;
@@ -87,24 +89,24 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
   const int vpair = tid % (kAttKV / 2), vch = tid / (kAttKV / 2);  // V: key pair and chunk (+ 8 i)
   auto fetch = [&](int kv0) {
     if (kv0 + kAttKV <= len) {  // whole tile inside the request: plain strided addresses
-      const uint16_t* kp = kbase + (size_t)(kv0 + krow) * h + kch * 8;
+      const uint16_t* kp = kbase + (size_t)(kv0 + krow) * hk + kch * 8;
 #pragma unroll
-      for (int i = 0; i < KITER; ++i) kreg[i] = ld16(kp + (size_t)i * (kAttThreads / CPR) * h);
-      const uint16_t* vp = vbase + (size_t)(kv0 + 2 * vpair) * h + vch * 8;
+      for (int i = 0; i < KITER; ++i) kreg[i] = ld16(kp + (size_t)i * (kAttThreads / CPR) * hk);
+      const uint16_t* vp = vbase + (size_t)(kv0 + 2 * vpair) * hk + vch * 8;
 #pragma unroll
       for (int i = 0; i < VITER; ++i) {
         vreg0[i] = ld16(vp + i * (kAttThreads / (kAttKV / 2)) * 8);
-        vreg1[i] = ld16(vp + h + i * (kAttThreads / (kAttKV / 2)) * 8);
+        vreg1[i] = ld16(vp + hk + i * (kAttThreads / (kAttKV / 2)) * 8);
       }
     } else {  // ragged tail: rows past the end repeat the last key (they are masked out below)
 #pragma unroll
       for (int i = 0; i < KITER; ++i)
-        kreg[i] = ld16(kbase + (size_t)min(kv0 + krow + i * (kAttThreads / CPR), len - 1) * h + kch * 8);
+        kreg[i] = ld16(kbase + (size_t)min(kv0 + krow + i * (kAttThreads / CPR), len - 1) * hk + kch * 8);
 #pragma unroll
       for (int i = 0; i < VITER; ++i) {
         const int ch = vch + i * (kAttThreads / (kAttKV / 2));
-        vreg0[i] = ld16(vbase + (size_t)min(kv0 + 2 * vpair, len - 1) * h + ch * 8);
-        vreg1[i] = ld16(vbase + (size_t)min(kv0 + 2 * vpair + 1, len - 1) * h + ch * 8);
+        vreg0[i] = ld16(vbase + (size_t)min(kv0 + 2 * vpair, len - 1) * hk + ch * 8);
+        vreg1[i] = ld16(vbase + (size_t)min(kv0 + 2 * vpair + 1, len - 1) * hk + ch * 8);
       }
     }
   };
@@ -232,9 +234,11 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
 int g_attn_force_order = -1;  // development switch: 0/1 force the workgroup order, -1 choose by grid size
 
 hipError_t launch_prefill_attention(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
-                                    int B, int max_seqlen, int n_heads, int head_dim, void* o,
+                                    int B, int max_seqlen, int n_heads, int n_kv_heads, int head_dim, void* o,
                                     hipStream_t stream) {
   if (B <= 0 || max_seqlen <= 0) return hipSuccess;
+  if (n_kv_heads <= 0 || n_heads % n_kv_heads != 0) return hipErrorInvalidValue;
+  const int kv_group = n_heads / n_kv_heads;
   const int n_qt = (max_seqlen + kAttQ - 1) / kAttQ;
   const long n_pairs = (long)B * n_heads;
   const long pairs_per_xcd = (n_pairs + 7) / 8;
@@ -246,11 +250,11 @@ hipError_t launch_prefill_attention(const void* q, const void* k, const void* v,
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
   if (head_dim == 128) {
     hipLaunchKernelGGL(prefill_attention_kernel<128>, grid, dim3(kAttThreads), 0, stream, (const uint16_t*)q,
-                       (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, scale_log2e,
+                       (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, kv_group, scale_log2e,
                        (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast);
   } else if (head_dim == 64) {
     hipLaunchKernelGGL(prefill_attention_kernel<64>, grid, dim3(kAttThreads), 0, stream, (const uint16_t*)q,
-                       (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, scale_log2e,
+                       (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, kv_group, scale_log2e,
                        (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast);
   } else {
     return hipErrorInvalidValue;

@@ -13,7 +13,7 @@
 #include "kernels.h"
 
 struct ds_ctx {
-  ds_model_cfg cfg;
+  ds_model_cfg cfg;  // n_kv_heads is normalised at creation: always the actual count, never 0
   char err[512];
   bool profile;
   struct Rec {
@@ -27,6 +27,10 @@ struct ds_ctx {
 namespace {
 
 constexpr int kSkinnyMaxRows = 256;
+
+// widths of the K/V rows and of the QKV projection output: n_kv s and (n + 2 n_kv) s
+int kv_width(const ds_model_cfg& c) { return c.n_kv_heads * c.head_dim; }
+int qkv_width(const ds_model_cfg& c) { return c.hidden + 2 * kv_width(c); }
 
 ds_status fail(ds_ctx* ctx, ds_status st, const char* fmt, ...) {
   if (ctx) {
@@ -137,7 +141,7 @@ size_t linear_ws(int rows, int in_f, int out_f) {
 }
 
 size_t max_gemm_ws(const ds_model_cfg& c, int rows) {
-  size_t a = linear_ws(rows, c.hidden, 3 * c.hidden);
+  size_t a = linear_ws(rows, c.hidden, qkv_width(c));
   size_t b = linear_ws(rows, c.hidden, c.hidden);
   size_t d = linear_ws(rows, c.hidden, c.ffn);
   size_t e = linear_ws(rows, c.ffn, c.hidden);
@@ -166,6 +170,8 @@ ds_status ds_create(const ds_model_cfg* cfg, ds_ctx** out) {
   *out = nullptr;
   if (cfg->hidden <= 0 || cfg->n_heads <= 0 || cfg->head_dim <= 0 || cfg->ffn <= 0) return DS_ERR_INVALID_ARG;
   if (cfg->hidden != cfg->n_heads * cfg->head_dim) return DS_ERR_INVALID_ARG;
+  const int n_kv = cfg->n_kv_heads == 0 ? cfg->n_heads : cfg->n_kv_heads;
+  if (n_kv < 0 || n_kv > cfg->n_heads || cfg->n_heads % n_kv != 0) return DS_ERR_INVALID_ARG;
   if (!(cfg->ln_eps > 0.f)) return DS_ERR_INVALID_ARG;
   if (cfg->head_dim != 64 && cfg->head_dim != 128) return DS_ERR_UNSUPPORTED;
   if (cfg->block_size != 16) return DS_ERR_UNSUPPORTED;
@@ -173,6 +179,7 @@ ds_status ds_create(const ds_model_cfg* cfg, ds_ctx** out) {
   ds_ctx* c = new (std::nothrow) ds_ctx();
   if (!c) return DS_ERR_INVALID_ARG;
   c->cfg = *cfg;
+  c->cfg.n_kv_heads = n_kv;
   c->err[0] = 0;
   c->profile = false;
   *out = c;
@@ -204,7 +211,7 @@ size_t ds_decode_workspace_bytes(const ds_ctx* ctx, int32_t max_batch, int32_t m
   if (!ctx || max_batch <= 0 || max_ctx <= 0) return 0;
   const ds_model_cfg& c = ctx->cfg;
   const size_t bh = align_up((size_t)max_batch * c.hidden * 2, 256);
-  const size_t b3h = align_up((size_t)max_batch * 3 * c.hidden * 2, 256);
+  const size_t b3h = align_up((size_t)max_batch * qkv_width(c) * 2, 256);
   const size_t bm = align_up((size_t)max_batch * c.ffn * 2, 256);
   const size_t att = align_up(ds::decode_attention_workspace_bytes(max_batch, c.n_heads, c.head_dim, max_ctx), 256);
   const size_t sk = align_up(max_gemm_ws(c, max_batch), 256);
@@ -308,7 +315,8 @@ ds_status ds_prefill_attention(ds_ctx* ctx, const void* q, const void* k, const 
     return fail(ctx, DS_ERR_INVALID_ARG, "ds_prefill_attention: pointers must be 16-byte aligned");
   hipStream_t s = static_cast<hipStream_t>(stream);
   DS_LAUNCH(ctx, s, DS_K_PREFILL_ATTN,
-            ds::launch_prefill_attention(q, k, v, cu_seqlens, B, max_seqlen, ctx->cfg.n_heads, ctx->cfg.head_dim, o, s));
+            ds::launch_prefill_attention(q, k, v, cu_seqlens, B, max_seqlen, ctx->cfg.n_heads, ctx->cfg.n_kv_heads,
+                                         ctx->cfg.head_dim, o, s));
   return DS_OK;
 }
 
@@ -348,12 +356,14 @@ ds_status ds_prefill(ds_ctx* ctx, const ds_layer_weights* w, const void* x, cons
     ep.bias = w->b_qkv;
     ep.out[0] = q; ep.out[1] = k_out; ep.out[2] = v_out;
     ep.seg_cols = h;
-    st = linear(ctx, a, w->w_qkv, t, h, 3 * h, ep, sk, s);
+    ep.seg_cols_kv = kv_width(c);
+    st = linear(ctx, a, w->w_qkv, t, h, qkv_width(c), ep, sk, s);
     if (st != DS_OK) return st;
   }
   // o = causal attention per request
   DS_LAUNCH(ctx, s, DS_K_PREFILL_ATTN,
-            ds::launch_prefill_attention(q, k_out, v_out, cu_seqlens, B, max_seqlen, c.n_heads, c.head_dim, o, s));
+            ds::launch_prefill_attention(q, k_out, v_out, cu_seqlens, B, max_seqlen, c.n_heads, c.n_kv_heads,
+                                         c.head_dim, o, s));
   // x1 = x + o W_o^T + b_o
   {
     ds::Epilogue ep;
@@ -400,7 +410,7 @@ ds_status ds_kv_migrate(ds_ctx* ctx, const void* k_src, const void* v_src, const
   hipStream_t s = static_cast<hipStream_t>(stream);
   DS_LAUNCH(ctx, s, DS_K_KV_MIGRATE,
             ds::launch_kv_migrate(k_src, v_src, cu_seqlens, B, max_seqlen, block_tables, max_blocks_per_seq,
-                                  k_cache, v_cache, ctx->cfg.n_heads, ctx->cfg.head_dim, s));
+                                  k_cache, v_cache, ctx->cfg.n_kv_heads, ctx->cfg.head_dim, s));
   return DS_OK;
 }
 
@@ -423,7 +433,7 @@ ds_status ds_decode_attention(ds_ctx* ctx, const void* q, const int32_t* kv_lens
   hipStream_t s = static_cast<hipStream_t>(stream);
   DS_LAUNCH(ctx, s, DS_K_DECODE_ATTN,
             ds::launch_decode_attention(q, c.hidden, kv_lens, 0, block_tables, B, max_blocks_per_seq, max_kv_len,
-                                        k_cache, v_cache, c.n_heads, c.head_dim, o, workspace, s));
+                                        k_cache, v_cache, c.n_heads, c.n_kv_heads, c.head_dim, o, workspace, s));
   return DS_OK;
 }
 
@@ -455,7 +465,8 @@ ds_status ds_decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, 
   void* a = ws.take((size_t)B * h * 2);
   void* o = ws.take((size_t)B * h * 2);
   void* x1 = ws.take((size_t)B * h * 2);
-  void* qkv = ws.take((size_t)B * 3 * h * 2);
+  const int hkv = kv_width(c), wqkv = qkv_width(c);
+  void* qkv = ws.take((size_t)B * wqkv * 2);
   void* u = ws.take((size_t)B * m * 2);
   void* att = ws.take(ds::decode_attention_workspace_bytes(B, c.n_heads, c.head_dim, max_ctx));
   void* sk = ws.take(0);
@@ -466,22 +477,23 @@ ds_status ds_decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, 
     // [q | k | v] = a W_qkv^T + b_qkv; the split-K reduction writes k, v straight into the cache
     ds::Epilogue ep;
     ep.bias = w->b_qkv;
-    ep.out[0] = qkv; ep.seg_cols = 3 * h;
+    ep.out[0] = qkv; ep.seg_cols = wqkv;
     ds::SkinnyFused fu;
     fu.kind = ds::SkinnyFused::kKvAppend;
     fu.ctx_lens = ctx_lens; fu.block_tables = block_tables; fu.max_blocks = max_blocks_per_seq;
-    fu.k_cache = k_cache; fu.v_cache = v_cache; fu.n_heads = c.n_heads; fu.head_dim = c.head_dim;
+    fu.k_cache = k_cache; fu.v_cache = v_cache;
+    fu.n_heads = c.n_heads; fu.n_kv_heads = c.n_kv_heads; fu.head_dim = c.head_dim;
     bool appended = false;
-    st = linear(ctx, a, w->w_qkv, B, h, 3 * h, ep, sk, s, &fu, &appended);
+    st = linear(ctx, a, w->w_qkv, B, h, wqkv, ep, sk, s, &fu, &appended);
     if (st != DS_OK) return st;
     if (!appended)
       DS_LAUNCH(ctx, s, DS_K_KV_APPEND,
-                ds::launch_kv_append(qkv16 + h, qkv16 + 2 * h, 3 * h, ctx_lens, block_tables, B, max_blocks_per_seq,
-                                     k_cache, v_cache, c.n_heads, c.head_dim, s));
+                ds::launch_kv_append(qkv16 + h, qkv16 + h + hkv, wqkv, ctx_lens, block_tables, B, max_blocks_per_seq,
+                                     k_cache, v_cache, c.n_kv_heads, c.head_dim, s));
   }
   DS_LAUNCH(ctx, s, DS_K_DECODE_ATTN,
-            ds::launch_decode_attention(qkv, 3 * h, ctx_lens, 1, block_tables, B, max_blocks_per_seq, max_ctx,
-                                        k_cache, v_cache, c.n_heads, c.head_dim, o, att, s));
+            ds::launch_decode_attention(qkv, wqkv, ctx_lens, 1, block_tables, B, max_blocks_per_seq, max_ctx,
+                                        k_cache, v_cache, c.n_heads, c.n_kv_heads, c.head_dim, o, att, s));
   {
     // x1 = x + o W_o^T + b_o, and f = LN2(x1) in the same reduction pass
     ds::Epilogue ep;

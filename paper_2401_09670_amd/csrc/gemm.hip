@@ -25,21 +25,21 @@ struct GemmParams {
   const uint16_t* bias;
   const uint16_t* residual;
   uint16_t* out[3];
-  int seg_cols;
+  int seg_cols, seg_cols_kv;  // widths of the first and of the other two output segments
   int M, N, K;
   int relu;
   int tiles_m, tiles_n;
   // Split-K (gridDim.y = S > 1): split s multiplies k-tiles s, s + S, ... and stores its fp32
   // accumulators to partial[s][M][N]; the epilogue then belongs to whoever adds the partials.
   float* partial;
-  // Decode QKV projection (N = 3 n_heads head_dim): with k_cache set, the K and V thirds of row m go to
-  // slot ctx_lens[m] of the paged cache [num_blocks, n_heads, 16, head_dim] instead of `out`.
+  // Decode QKV projection (N = (n_heads + 2 n_kv_heads) head_dim): with k_cache set, the K and V parts of
+  // row m go to slot ctx_lens[m] of the paged cache [num_blocks, n_kv_heads, 16, head_dim] instead of `out`.
   const int32_t* ctx_lens;
   const int32_t* block_tables;
   int max_blocks;
   uint16_t* k_cache;
   uint16_t* v_cache;
-  int n_heads, head_dim;
+  int n_heads, n_kv_heads, head_dim;
 };
 
 // Workgroup ids are dealt round-robin to the 8 XCDs (each with a private L2).
@@ -352,17 +352,19 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
         o[j] = pack_bf16(e0, e1);
       }
       if (row < p.M && n < p.N) {
-        const int hq = p.n_heads * p.head_dim;
+        const int hq = p.n_heads * p.head_dim, hkv = p.n_kv_heads * p.head_dim;
         if (EPI == kEpiKvScatter && n >= hq) {  // this step's new K / V row of sequence `row`: straight into its page
-          const int which = n >= 2 * hq;
-          const int col = n - hq * (1 + which);
+          const int which = n >= hq + hkv;
+          const int col = n - hq - which * hkv;
           const int head = col / p.head_dim, d = col - head * p.head_dim;
           const int pos = p.ctx_lens[row];
           const int blk = p.block_tables[(size_t)row * p.max_blocks + pos / 16];
-          st16((which ? p.v_cache : p.k_cache) + (((size_t)blk * p.n_heads + head) * 16 + (pos % 16)) * p.head_dim + d, o);
+          st16((which ? p.v_cache : p.k_cache) + (((size_t)blk * p.n_kv_heads + head) * 16 + (pos % 16)) * p.head_dim + d, o);
         } else {
-          const int seg = (n >= p.seg_cols) + (n >= 2 * p.seg_cols);
-          st16(p.out[seg] + (size_t)row * p.seg_cols + (n - seg * p.seg_cols), o);
+          const int seg = (n >= p.seg_cols) + (n >= p.seg_cols + p.seg_cols_kv);
+          const int ld = seg == 0 ? p.seg_cols : p.seg_cols_kv;
+          const int first = seg == 0 ? 0 : p.seg_cols + (seg - 1) * p.seg_cols_kv;
+          st16(p.out[seg] + (size_t)row * ld + (n - first), o);
         }
       }
     }
@@ -456,7 +458,9 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
                        hipStream_t stream, void* workspace, const SkinnyFused* fused, bool* fused_done) {
   if (fused_done) *fused_done = false;
   if (M <= 0 || N <= 0) return hipSuccess;
-  if (K < kBK || K % kBK != 0 || N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0) return hipErrorInvalidValue;
+  if (K < kBK || K % kBK != 0 || N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0 || ep.seg_cols_kv < 0 ||
+      ep.seg_cols_kv % 8 != 0)
+    return hipErrorInvalidValue;
   if (ep.residual && ep.seg_cols != N) return hipErrorInvalidValue;
   GemmParams p;
   p.X = (const uint16_t*)X;
@@ -465,23 +469,25 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
   p.residual = (const uint16_t*)ep.residual;
   for (int i = 0; i < 3; ++i) p.out[i] = (uint16_t*)ep.out[i];
   p.seg_cols = ep.seg_cols;
+  p.seg_cols_kv = ep.seg_cols_kv > 0 ? ep.seg_cols_kv : ep.seg_cols;
   p.M = M; p.N = N; p.K = K;
   p.relu = ep.relu;
   p.tiles_m = p.tiles_n = 0;
   p.partial = nullptr;
   p.ctx_lens = nullptr; p.block_tables = nullptr; p.max_blocks = 0;
-  p.k_cache = nullptr; p.v_cache = nullptr; p.n_heads = 0; p.head_dim = 0;
+  p.k_cache = nullptr; p.v_cache = nullptr; p.n_heads = 0; p.n_kv_heads = 0; p.head_dim = 0;
   GemmPlan pl = gemm_plan(M, N, K);
   if (pl.splits > 1 && workspace == nullptr) pl.splits = 1;  // no room for partials: slower, still right
   const bool want_kv = fused && fused->kind == SkinnyFused::kKvAppend && ep.seg_cols == N && !ep.relu &&
-                       !ep.residual && N == 3 * fused->n_heads * fused->head_dim && fused->head_dim % 8 == 0;
+                       !ep.residual && N == (fused->n_heads + 2 * fused->n_kv_heads) * fused->head_dim &&
+                       fused->head_dim % 8 == 0;
   if (pl.splits > 1) {
     p.partial = (float*)workspace;
   } else if (want_kv && (pl.variant == 2 || pl.variant == 4)) {
     // unsplit (decode-sized tiles only): the tile kernel's own epilogue scatters K and V into the cache
     p.ctx_lens = fused->ctx_lens; p.block_tables = fused->block_tables; p.max_blocks = fused->max_blocks;
     p.k_cache = (uint16_t*)fused->k_cache; p.v_cache = (uint16_t*)fused->v_cache;
-    p.n_heads = fused->n_heads; p.head_dim = fused->head_dim;
+    p.n_heads = fused->n_heads; p.n_kv_heads = fused->n_kv_heads; p.head_dim = fused->head_dim;
     if (fused_done) *fused_done = true;
   }
   hipError_t e;

@@ -35,7 +35,7 @@ struct SkinnyParams {
   const uint16_t* bias;
   const uint16_t* residual;
   uint16_t* out[3];
-  int seg_cols;
+  int seg_cols, seg_cols_kv;  // widths of the first and of the other two output segments
   int M, N, K;
   int relu;
   float* partial;  // [KSPLIT][M][N] fp32 when gridDim.y > 1
@@ -246,11 +246,13 @@ __global__ __launch_bounds__(kSkThreads) void skinny_gemm_kernel(const SkinnyPar
         v0 += bf16_lo(rr[0]); v1 += bf16_hi(rr[0]);
         v2 += bf16_lo(rr[1]); v3 += bf16_hi(rr[1]);
       }
-      const int seg = (n >= p.seg_cols) + (n >= 2 * p.seg_cols);
+      const int seg = (n >= p.seg_cols) + (n >= p.seg_cols + p.seg_cols_kv);
+      const int ld = seg == 0 ? p.seg_cols : p.seg_cols_kv;
+      const int first = seg == 0 ? 0 : p.seg_cols + (seg - 1) * p.seg_cols_kv;
       u32x2 ov;
       ov[0] = pack_bf16(v0, v1);
       ov[1] = pack_bf16(v2, v3);
-      *reinterpret_cast<u32x2*>(p.out[seg] + (size_t)m * p.seg_cols + (n - seg * p.seg_cols)) = ov;
+      *reinterpret_cast<u32x2*>(p.out[seg] + (size_t)m * ld + (n - first)) = ov;
     }
   }
 }
@@ -310,11 +312,13 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(const SkinnyParams p
       v[2 * j + 1] += bf16_hi(rr[j]);
     }
   }
-  const int seg = (n >= p.seg_cols) + (n >= 2 * p.seg_cols);
+  const int seg = (n >= p.seg_cols) + (n >= p.seg_cols + p.seg_cols_kv);
+  const int ld = seg == 0 ? p.seg_cols : p.seg_cols_kv;
+  const int first = seg == 0 ? 0 : p.seg_cols + (seg - 1) * p.seg_cols_kv;
   u32x4 ov;
 #pragma unroll
   for (int j = 0; j < 4; ++j) ov[j] = pack_bf16(v[2 * j], v[2 * j + 1]);
-  st16(p.out[seg] + (size_t)m * p.seg_cols + (n - seg * p.seg_cols), ov);
+  st16(p.out[seg] + (size_t)m * ld + (n - first), ov);
 }
 
 // The same reduction, one workgroup per output row, followed by LayerNorm of that row: writes
@@ -414,15 +418,15 @@ __global__ __launch_bounds__(kRedLnThreads) void skinny_reduce_ln_kernel(const S
   }
 }
 
-// The same reduction for the decode QKV projection (N = 3h, one output buffer with row stride 3h):
-// the Q third is written to out[0]; the K and V thirds are this step's new cache rows and go to
-// slot ctx_lens[m] of the paged cache [num_blocks, heads, 16, head_dim].
+// The same reduction for the decode QKV projection (N = (n + 2 n_kv) s, one output buffer with row stride N):
+// the Q part is written to out[0]; the K and V parts are this step's new cache rows and go to
+// slot ctx_lens[m] of the paged cache [num_blocks, n_kv, 16, s].
 __global__ __launch_bounds__(256) void skinny_reduce_kv_kernel(const SkinnyParams p, int n_splits,
                                                                const int32_t* __restrict__ ctx_lens,
                                                                const int32_t* __restrict__ block_tables,
                                                                int max_blocks, uint16_t* __restrict__ k_cache,
                                                                uint16_t* __restrict__ v_cache, int n_heads,
-                                                               int head_dim) {
+                                                               int n_kv_heads, int head_dim) {
   const int chunks_per_row = p.N >> 3;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (long)p.M * chunks_per_row) return;
@@ -441,17 +445,17 @@ __global__ __launch_bounds__(256) void skinny_reduce_kv_kernel(const SkinnyParam
   u32x4 ov;
 #pragma unroll
   for (int j = 0; j < 4; ++j) ov[j] = pack_bf16(v[2 * j], v[2 * j + 1]);
-  const int h = n_heads * head_dim;
+  const int h = n_heads * head_dim, hkv = n_kv_heads * head_dim;
   if (n < h) {
     st16(p.out[0] + (size_t)m * p.N + n, ov);
     return;
   }
-  const int which = n >= 2 * h;
-  const int col = n - h * (1 + which);
+  const int which = n >= h + hkv;
+  const int col = n - h - which * hkv;
   const int head = col / head_dim, d = col - head * head_dim;
   const int pos = ctx_lens[m];
   const int blk = block_tables[(size_t)m * max_blocks + pos / 16];
-  uint16_t* dst = (which ? v_cache : k_cache) + (((size_t)blk * n_heads + head) * 16 + (pos % 16)) * head_dim + d;
+  uint16_t* dst = (which ? v_cache : k_cache) + (((size_t)blk * n_kv_heads + head) * 16 + (pos % 16)) * head_dim + d;
   st16(dst, ov);
 }
 
@@ -560,6 +564,7 @@ hipError_t launch_skinny_argmax(const void* X, const void* W, int M, int N, int 
   p.residual = nullptr;
   for (int i = 0; i < 3; ++i) p.out[i] = nullptr;
   p.seg_cols = N;
+  p.seg_cols_kv = N;
   p.M = M; p.N = N; p.K = K;
   p.relu = 0;
   p.partial = nullptr;
@@ -575,7 +580,8 @@ hipError_t launch_skinny_argmax(const void* X, const void* W, int M, int N, int 
 hipError_t launch_splitk_reduce(const float* partial, int splits, int M, int N, const Epilogue& ep,
                                 const SkinnyFused* fused, bool* fused_done, hipStream_t stream) {
   if (fused_done) *fused_done = false;
-  if (N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0) return hipErrorInvalidValue;
+  if (N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0 || ep.seg_cols_kv < 0 || ep.seg_cols_kv % 8 != 0)
+    return hipErrorInvalidValue;
   SkinnyParams p;
   p.X = nullptr;
   p.W = nullptr;
@@ -583,6 +589,7 @@ hipError_t launch_splitk_reduce(const float* partial, int splits, int M, int N, 
   p.residual = (const uint16_t*)ep.residual;
   for (int i = 0; i < 3; ++i) p.out[i] = (uint16_t*)ep.out[i];
   p.seg_cols = ep.seg_cols;
+  p.seg_cols_kv = ep.seg_cols_kv > 0 ? ep.seg_cols_kv : ep.seg_cols;
   p.M = M; p.N = N; p.K = 0;
   p.relu = ep.relu;
   p.partial = const_cast<float*>(partial);
@@ -600,10 +607,10 @@ hipError_t launch_splitk_reduce(const float* partial, int splits, int M, int N, 
                          (uint16_t*)fused->ln_out);
     if (fused_done) *fused_done = true;
   } else if (fused && fused->kind == SkinnyFused::kKvAppend && ep.seg_cols == N && !ep.relu && !ep.residual &&
-             N == 3 * fused->n_heads * fused->head_dim) {
+             N == (fused->n_heads + 2 * fused->n_kv_heads) * fused->head_dim) {
     hipLaunchKernelGGL(skinny_reduce_kv_kernel, dim3(blocks), dim3(256), 0, stream, p, splits, fused->ctx_lens,
                        fused->block_tables, fused->max_blocks, (uint16_t*)fused->k_cache,
-                       (uint16_t*)fused->v_cache, fused->n_heads, fused->head_dim);
+                       (uint16_t*)fused->v_cache, fused->n_heads, fused->n_kv_heads, fused->head_dim);
     if (fused_done) *fused_done = true;
   } else {
     hipLaunchKernelGGL(skinny_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p, splits);
@@ -615,7 +622,8 @@ hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K,
                               void* workspace, hipStream_t stream, const SkinnyFused* fused, bool* fused_done) {
   if (fused_done) *fused_done = false;
   if (M <= 0 || N <= 0) return hipSuccess;
-  if (M > 256 || K % kSkKS != 0 || N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0)
+  if (M > 256 || K % kSkKS != 0 || N % 8 != 0 || ep.seg_cols <= 0 || ep.seg_cols % 8 != 0 || ep.seg_cols_kv < 0 ||
+      ep.seg_cols_kv % 8 != 0)
     return hipErrorInvalidValue;
   if (ep.residual && ep.seg_cols != N) return hipErrorInvalidValue;
   SkinnyParams p;
@@ -625,6 +633,7 @@ hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K,
   p.residual = (const uint16_t*)ep.residual;
   for (int i = 0; i < 3; ++i) p.out[i] = (uint16_t*)ep.out[i];
   p.seg_cols = ep.seg_cols;
+  p.seg_cols_kv = ep.seg_cols_kv > 0 ? ep.seg_cols_kv : ep.seg_cols;
   p.M = M; p.N = N; p.K = K;
   p.relu = ep.relu;
   const SkinnyPlan pl = skinny_plan(M, N, K);

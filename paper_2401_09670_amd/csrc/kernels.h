@@ -14,15 +14,17 @@ hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, 
                             const int32_t* row_index = nullptr);
 
 // Epilogue of both GEMM paths: out = act(acc + bias) + residual, written as bf16.
-// The N output columns may be cut into up to three equal segments of
-// `seg_cols` columns that go to different buffers (Q | K | V); residual is
-// only allowed with a single segment.
+// The N output columns may be cut into up to three segments that go to
+// different buffers (Q | K | V): the first `seg_cols` wide, the other two
+// `seg_cols_kv` wide (0 = as wide as the first); each buffer's row stride is
+// its segment width.  Residual is only allowed with a single segment.
 struct Epilogue {
   const void* bias = nullptr;      // [N] bf16 or null
   const void* residual = nullptr;  // [M, N] bf16 or null
   int relu = 0;
   void* out[3] = {nullptr, nullptr, nullptr};
-  int seg_cols = 0;  // N / number of segments; row stride of each out buffer
+  int seg_cols = 0;     // width (= row stride) of out[0]
+  int seg_cols_kv = 0;  // width (= row stride) of out[1] and out[2]; 0 = seg_cols
 };
 
 struct SkinnyFused;
@@ -38,8 +40,9 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
 
 // Work that the decode GEMM's split-K reduction can absorb (saves a launch each):
 //  kLayerNorm: after out = act(..) + residual is written, also write ln_out = LN(out) (row-wise).
-//  kKvAppend : columns [0, h) go to out[0] as usual; columns [h, 2h) / [2h, 3h) are this step's K / V
-//              rows and go straight into the paged cache at position ctx_lens[row].
+//  kKvAppend : columns [0, n s) go to out[0] as usual; the next n_kv s columns and the n_kv s after
+//              them are this step's K / V rows and go straight into the paged cache
+//              [num_blocks, n_kv, 16, s] at position ctx_lens[row].
 struct SkinnyFused {
   enum Kind { kNone = 0, kLayerNorm = 1, kKvAppend = 2 } kind = kNone;
   const void* ln_gamma = nullptr;
@@ -51,7 +54,7 @@ struct SkinnyFused {
   int max_blocks = 0;
   void* k_cache = nullptr;
   void* v_cache = nullptr;
-  int n_heads = 0, head_dim = 0;
+  int n_heads = 0, n_kv_heads = 0, head_dim = 0;
 };
 
 hipError_t launch_splitk_reduce(const float* partial, int splits, int M, int N, const Epilogue& ep,
@@ -78,9 +81,10 @@ hipError_t launch_skinny_argmax(const void* X, const void* W, int M, int N, int 
 hipError_t launch_embed(const int32_t* token_ids, const int32_t* positions, const void* tok_emb, int vocab,
                         const void* pos_emb, int n_pos, int rows, int h, void* x, hipStream_t stream);
 
-// Causal attention within each packed request; q,k,v,o rows have `n_heads*head_dim` elements.
+// Causal attention within each packed request; q,o rows have `n_heads*head_dim` elements, k,v rows
+// `n_kv_heads*head_dim` (query head j reads key/value head j / (n_heads/n_kv_heads)).
 hipError_t launch_prefill_attention(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
-                                    int B, int max_seqlen, int n_heads, int head_dim, void* o,
+                                    int B, int max_seqlen, int n_heads, int n_kv_heads, int head_dim, void* o,
                                     hipStream_t stream);
 
 // contiguous [t,n,s] -> paged [num_blocks,n,16,s] for K and V in one launch
@@ -99,7 +103,7 @@ size_t decode_attention_workspace_bytes(int B, int n_heads, int head_dim, int ma
 int decode_attention_splits(int B, int n_heads, int max_kv_len);
 hipError_t launch_decode_attention(const void* q, int q_stride, const int32_t* kv_lens, int kv_len_add,
                                    const int32_t* block_tables, int B, int max_blocks, int max_kv_len,
-                                   const void* k_cache, const void* v_cache, int n_heads, int head_dim,
-                                   void* o, void* workspace, hipStream_t stream);
+                                   const void* k_cache, const void* v_cache, int n_heads, int n_kv_heads,
+                                   int head_dim, void* o, void* workspace, hipStream_t stream);
 
 }  // namespace ds

@@ -35,7 +35,8 @@ def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
 
 
 def make_ctx(shape) -> binding.Context:
-    return binding.Context(shape.hidden, shape.n_heads, shape.head_dim, shape.ffn, shape.block_size, shape.ln_eps)
+    return binding.Context(shape.hidden, shape.n_heads, shape.head_dim, shape.ffn, shape.block_size, shape.ln_eps,
+                           shape.n_kv_heads)
 
 
 def workspace(nbytes: int) -> torch.Tensor:
@@ -67,7 +68,8 @@ def dev_layer_weights(shape, seed: int):
     h, m = shape.hidden, shape.ffn
     w = {
         "ln1_g": dev_normal_bits((h,), 0.02, seed + 1, 1.0), "ln1_b": dev_normal_bits((h,), 0.02, seed + 2),
-        "w_qkv": dev_normal_bits((3 * h, h), 0.02, seed + 3), "b_qkv": dev_normal_bits((3 * h,), 0.02, seed + 4),
+        "w_qkv": dev_normal_bits((shape.qkv_width, h), 0.02, seed + 3),
+        "b_qkv": dev_normal_bits((shape.qkv_width,), 0.02, seed + 4),
         "w_o": dev_normal_bits((h, h), 0.02, seed + 5), "b_o": dev_normal_bits((h,), 0.02, seed + 6),
         "ln2_g": dev_normal_bits((h,), 0.02, seed + 7, 1.0), "ln2_b": dev_normal_bits((h,), 0.02, seed + 8),
         "w_fc1": dev_normal_bits((m, h), 0.02, seed + 9), "b_fc1": dev_normal_bits((m,), 0.02, seed + 10),

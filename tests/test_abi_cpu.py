@@ -32,12 +32,20 @@ def test_create_validates_config():
            dict(hidden=256, n_heads=4, head_dim=64, ffn=1024, block_size=32, ln_eps=1e-5),   # page size
            dict(hidden=250, n_heads=4, head_dim=64, ffn=1024, block_size=16, ln_eps=1e-5),   # h != n*s
            dict(hidden=256, n_heads=4, head_dim=64, ffn=1000, block_size=16, ln_eps=1e-5),   # ffn % 64
-           dict(hidden=256, n_heads=4, head_dim=64, ffn=1024, block_size=16, ln_eps=0.0)]
+           dict(hidden=256, n_heads=4, head_dim=64, ffn=1024, block_size=16, ln_eps=0.0),
+           dict(hidden=256, n_heads=4, head_dim=64, ffn=1024, block_size=16, ln_eps=1e-5, n_kv_heads=3),   # 4 % 3
+           dict(hidden=256, n_heads=4, head_dim=64, ffn=1024, block_size=16, ln_eps=1e-5, n_kv_heads=8),   # > n
+           dict(hidden=256, n_heads=4, head_dim=64, ffn=1024, block_size=16, ln_eps=1e-5, n_kv_heads=-1)]
     for kw in bad:
         cfg = binding.ModelCfg(**kw)
         assert lib.ds_create(ctypes.byref(cfg), ctypes.byref(h)) != binding.DS_OK
         assert not h.value
     assert lib.ds_create(None, ctypes.byref(h)) == 1
+    for n_kv in (0, 1, 2, 4):   # 0 = as many as query heads; divisors of n = grouped-query attention
+        binding.Context(256, 4, 64, 1024, n_kv_heads=n_kv).close()
+    # fewer key/value heads shrink the QKV projection, hence the decode workspace
+    assert binding.Context(256, 4, 64, 1024, n_kv_heads=1).ds_decode_workspace_bytes(8, 64) < \
+        binding.Context(256, 4, 64, 1024).ds_decode_workspace_bytes(8, 64)
 
 
 def test_host_argument_checks_return_status():

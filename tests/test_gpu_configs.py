@@ -21,7 +21,9 @@ def _prefill_and_check(shape, lw, w32, lens, seed, sample_seqs, rows_per_seq=6):
     t, h = int(sum(lens)), shape.hidden
     x = gu.dev_normal_bits((t, h), 1.0, seed + 100)
     y = torch.empty(t, h, dtype=torch.bfloat16, device="cuda")
-    k_out, v_out = torch.empty_like(y), torch.empty_like(y)
+    hkv = shape.kv_heads * shape.head_dim
+    k_out = torch.empty(t, hkv, dtype=torch.bfloat16, device="cuda")
+    v_out = torch.empty_like(k_out)
     ws = gu.workspace(ctx.ds_prefill_workspace_bytes(t))
     ctx.ds_prefill(lw, x, gu.i32_dev(synth.cu_seqlens(lens)), len(lens), t, int(max(lens)), y, k_out, v_out, ws)
     torch.cuda.synchronize()
@@ -36,21 +38,21 @@ def _prefill_and_check(shape, lw, w32, lens, seed, sample_seqs, rows_per_seq=6):
         yg = gu.to_f64(y[r0:r0 + l])
         assert gu.rel_err(yg[rows], yr) < TOL, (i, l)
         assert gu.update_ok(yg[rows], yr.astype(np.float64), xs[rows].astype(np.float64)), (i, l)
-        assert gu.rel_err(gu.to_f64(k_out[r0:r0 + l]), kr.reshape(l, h)) < TOL
-        assert gu.rel_err(gu.to_f64(v_out[r0:r0 + l]), vr.reshape(l, h)) < TOL
+        assert gu.rel_err(gu.to_f64(k_out[r0:r0 + l]), kr.reshape(l, hkv)) < TOL
+        assert gu.rel_err(gu.to_f64(v_out[r0:r0 + l]), vr.reshape(l, hkv)) < TOL
     return ctx, k_out, v_out
 
 
 def _migrate_and_check(ctx, shape, k_out, v_out, lens, seed, extra=1):
     t = int(sum(lens))
     bt, nblk = synth.make_block_tables([int(l) + extra for l in lens], 16, seed)
-    kc = torch.full((nblk, shape.n_heads, 16, shape.head_dim), 3.0, dtype=torch.bfloat16, device="cuda")
+    kc = torch.full((nblk, shape.kv_heads, 16, shape.head_dim), 3.0, dtype=torch.bfloat16, device="cuda")
     vc = torch.full_like(kc, 5.0)
     ctx.ds_kv_migrate(k_out, v_out, gu.i32_dev(synth.cu_seqlens(lens)), len(lens), t, int(max(lens)), gu.i32_dev(bt),
                       bt.shape[1], kc, vc, nblk)
     torch.cuda.synchronize()
     kref, vref = gu.to_bits(torch.full_like(kc, 3.0)), gu.to_bits(torch.full_like(vc, 5.0))
-    orc.kv_migrate(gu.to_bits(k_out).reshape(t, shape.n_heads, -1), gu.to_bits(v_out).reshape(t, shape.n_heads, -1),
+    orc.kv_migrate(gu.to_bits(k_out).reshape(t, shape.kv_heads, -1), gu.to_bits(v_out).reshape(t, shape.kv_heads, -1),
                    [int(l) for l in lens], bt, kref, vref)
     assert np.array_equal(gu.to_bits(kc), kref)
     assert np.array_equal(gu.to_bits(vc), vref)
@@ -59,13 +61,14 @@ def _migrate_and_check(ctx, shape, k_out, v_out, lens, seed, extra=1):
 def _decode_and_check(shape, lw, w32, ctx_lens, seed, sample, steps=1):
     ctx = gu.make_ctx(shape)
     B, h, n, s = len(ctx_lens), shape.hidden, shape.n_heads, shape.head_dim
+    nk = shape.kv_heads
     bt, nblk = synth.make_block_tables([int(c) + steps for c in ctx_lens], 16, seed)
     # cache contents are an input: every page filled with seeded N(0,1) values on the device
-    kc = gu.dev_normal_bits((nblk, n, 16, s), 1.0, seed + 200)
-    vc = gu.dev_normal_bits((nblk, n, 16, s), 1.0, seed + 201)
+    kc = gu.dev_normal_bits((nblk, nk, 16, s), 1.0, seed + 200)
+    vc = gu.dev_normal_bits((nblk, nk, 16, s), 1.0, seed + 201)
     # oracle side: its own small float32 cache holding only the sampled sequences (paging is an index map)
     sbt, snblk = synth.make_block_tables([int(ctx_lens[i]) + steps for i in sample], 16, seed + 1)
-    okc = np.zeros((snblk, n, 16, s), dtype=np.float32)
+    okc = np.zeros((snblk, nk, 16, s), dtype=np.float32)
     ovc = np.zeros_like(okc)
     for r, i in enumerate(sample):
         nb = synth.blocks_needed(int(ctx_lens[i]) + steps, 16)
@@ -223,3 +226,29 @@ def test_decode_step_wide_batches(gpu, hidden, n_heads, ffn, B):
     sample = sorted(set([0, B - 1, int(np.argmax(ctxs)), int(np.argmin(ctxs))] +
                         [int(i) for i in np.random.default_rng(seed).integers(0, B, size=12)]))
     _decode_and_check(shape, lw, w64, ctxs, seed, sample, steps=3)
+
+
+@pytest.mark.parametrize("name,hidden,n_heads,n_kv,head_dim,ffn", [
+    ("gqa-small", 512, 8, 2, 64, 1024),          # every row and element against the fp64 oracle
+    ("mqa-small", 256, 2, 1, 128, 512),          # one key/value head for all query heads
+    ("llama2-70b-like", 8192, 64, 8, 128, 28672),  # that model's attention geometry (sampled rows)
+])
+def test_grouped_query_attention_layer(gpu, name, hidden, n_heads, n_kv, head_dim, ffn):
+    """Fewer key/value heads than query heads (grouped-query attention, named in Sec. 3.2): the QKV
+    projection is (n + 2 n_kv) s wide, K/V rows and the paged cache have n_kv heads, query head j reads
+    key/value head j / (n / n_kv).  Prefill, the bit-exact hand-off and decode steps of both GEMM kernels
+    (64 and 150 rows)."""
+    shape = synth.ModelShape(hidden=hidden, n_heads=n_heads, head_dim=head_dim, ffn=ffn, n_kv_heads=n_kv)
+    seed = 777 + hidden
+    lw, wdev = gu.dev_layer_weights(shape, seed)
+    small = hidden <= 512
+    wref = orc.weights_from_bits(gu.host_weights(wdev), np.float64 if small else np.float32)
+    lens = [70, 5, 131, 1] if small else [300, 17, 129]
+    ctx, k_out, v_out = _prefill_and_check(shape, lw, wref, lens, seed, list(range(len(lens))) if small else [1, 2],
+                                           rows_per_seq=200 if small else 5)
+    assert k_out.shape[1] == n_kv * head_dim
+    _migrate_and_check(ctx, shape, k_out, v_out, lens, seed)
+    for B in (64, 150):
+        ctxs = synth.uniform_lengths(B, 1, 300, seed, stream=B)
+        sample = list(range(B)) if small else [0, B - 1, int(np.argmax(ctxs)), int(np.argmin(ctxs))]
+        _decode_and_check(shape, lw, wref, ctxs, seed + B, sample, steps=2)
