@@ -43,6 +43,14 @@ struct SkinnyParams {
   // accumulator of this workgroup's columns and its column go to amax_val / amax_idx [gridDim.x][M].
   float* amax_val = nullptr;
   int32_t* amax_idx = nullptr;
+  // Wave-private-ring kernel only: with kv_k_cache set (decode QKV projection, N = (n + 2 n_kv) s) the K and V
+  // parts of row m go to slot kv_ctx_lens[m] of the paged cache [num_blocks, n_kv, 16, s] instead of `out`.
+  const int32_t* kv_ctx_lens = nullptr;
+  const int32_t* kv_block_tables = nullptr;
+  int kv_max_blocks = 0;
+  uint16_t* kv_k_cache = nullptr;
+  uint16_t* kv_v_cache = nullptr;
+  int kv_n_heads = 0, kv_n_kv_heads = 0, kv_head_dim = 0;
 };
 
 template <int VM>
@@ -252,6 +260,151 @@ __global__ __launch_bounds__(kSkThreads) void skinny_gemm_kernel(const SkinnyPar
       u32x2 ov;
       ov[0] = pack_bf16(v0, v1);
       ov[1] = pack_bf16(v2, v3);
+      *reinterpret_cast<u32x2*>(p.out[seg] + (size_t)m * ld + (n - first)) = ov;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Wave-private rings (up to 64 rows, wide N): the shape for which the ring kernel above needs
+// split-K only to find 256 workgroups, and then pays for it twice (≈ 5 us of partial-sum stores at
+// the end of every workgroup at once, ≈ 5 us for the reduce launch).  Measured on this chip: what a
+// streaming kernel needs is not many bytes in flight per CU but several streams per CU that do not
+// stall together - two independent 16 KB streams per CU reach 5.7 TB/s, one 64 KB stream 5.3.
+//
+// So: a workgroup (4 waves) owns 64 output columns over the whole K; its waves split K between them
+// 64-wide slab by slab (wave w takes slabs w, w+4, ...) and each wave runs its OWN two-stage
+// direct-to-LDS ring [64 activation rows | 64 weight rows] x 128 bytes, waiting on nothing but its
+// own loads - no barrier in the loop, four desynchronised streams per CU.  The four waves' 64 x 64
+// fp32 tiles are added through LDS at the end (fixed order) and wave w finishes column tile w.
+// grid = N / 64 workgroups, no partial sums in global memory, no second launch.
+// ---------------------------------------------------------------------------------------------
+constexpr int kWrThreads = 256;
+constexpr int kWrKS = 64;  // k elements per slab
+
+// NT = weight row tiles of 16 per workgroup (4 or 5: 64 or 80 output columns, whichever tiles N into
+// fewer rounds of 256 workgroups).
+template <int NT>
+__global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyParams p) {
+  constexpr int kWrBN = 16 * NT;
+  constexpr int kWrStageElems = (64 + kWrBN) * kWrKS;  // [64 X rows | BN W rows] x 64 k
+  constexpr int kWrLoads = (64 + kWrBN) / 8;           // wave-level loads (8 rows x 128 B) per slab
+  extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n0 = blockIdx.x * kWrBN;
+  const int K = p.K;
+  const int slabs_total = K / kWrKS;
+  const int ns = (slabs_total - wave + 3) / 4;  // this wave's slabs: wave, wave + 4, ...  (>= 1: K >= 256)
+
+  // load j of a slab covers stage rows 8j .. 8j+7 (rows 0..63 = X, 64..127 = W); lane: row 8j + lane/8,
+  // 16-byte chunk (lane%8) ^ ((row >> 1) & 7) - the swizzle that makes the fragment reads conflict-free
+  const uint16_t* src[kWrLoads];
+#pragma unroll
+  for (int j = 0; j < kWrLoads; ++j) {
+    const int r = 8 * j + (lane >> 3);
+    const int sw = ((lane & 7) ^ ((r >> 1) & 7)) * 8;
+    if (r < 64) src[j] = p.X + (size_t)min(r, p.M - 1) * K + (size_t)wave * kWrKS + sw;
+    else src[j] = p.W + (size_t)min(n0 + r - 64, p.N - 1) * K + (size_t)wave * kWrKS + sw;
+  }
+  uint16_t* ring = lds + wave * 2 * kWrStageElems;
+  auto request = [&](int i, int st) {  // this wave's slab i (clamped: a harmless re-load) into its stage st
+    const int ofs = min(i, ns - 1) * 4 * kWrKS;
+    uint16_t* dst = ring + st * kWrStageElems;
+#pragma unroll
+    for (int j = 0; j < kWrLoads; ++j)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ofs),
+                                       (__attribute__((address_space(3))) void*)(dst + j * 512), 16, 0, 0);
+  };
+
+  floatx4 acc[NT][4];  // [weight row tile a][activation row tile t]
+#pragma unroll
+  for (int a = 0; a < NT; ++a)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[a][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+  // fragment of k-step s (32 k): lane (row r = lane%16 of a 16-row tile, quarter q = lane/16) reads chunk 4s+q
+  int fo[2];
+#pragma unroll
+  for (int s2 = 0; s2 < 2; ++s2)
+    fo[s2] = (lane & 15) * kWrKS + (((4 * s2 + (lane >> 4)) ^ (((lane & 15) >> 1) & 7)) * 8);
+
+  request(0, 0);
+  for (int i = 0; i < ns; ++i) {
+    const int st = i & 1;
+    request(i + 1, st ^ 1);          // the other stage was last read in iteration i-1
+    sk_wait_vmcnt<kWrLoads>();       // slab i has landed (slab i+1 may still fly)
+    const uint16_t* sb = ring + st * kWrStageElems;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      u32x4 xf[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) xf[t] = *reinterpret_cast<const u32x4*>(sb + t * 16 * kWrKS + fo[s2]);
+#pragma unroll
+      for (int a = 0; a < NT; ++a) {
+        const u32x4 wf = *reinterpret_cast<const u32x4*>(sb + (64 + a * 16) * kWrKS + fo[s2]);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          acc[a][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf),
+                                                              __builtin_bit_cast(bf16x8, xf[t]), acc[a][t], 0, 0, 0);
+      }
+    }
+  }
+  sk_wait_vmcnt<0>();  // the clamped re-load of the last iteration must not land in the reduction area
+  __syncthreads();     // every wave is done with its ring: reuse the LDS to add the four waves' tiles
+  {
+    floatx4* red = reinterpret_cast<floatx4*>(lds);  // [wave][a][t][64 lanes]
+#pragma unroll
+    for (int a = 0; a < NT; ++a)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) red[((wave * NT + a) * 4 + t) * 64 + lane] = acc[a][t];
+    __syncthreads();
+  }
+  // wave w finishes weight row tiles a = w (and w + 4): the four waves' tiles are added in wave order.
+  // Lane: row m = 16t + lane%16, columns n = n0 + 16a + 4*(lane/16) + 0..3.
+  const floatx4* red = reinterpret_cast<const floatx4*>(lds);
+  for (int a = wave; a < NT; a += 4) {
+    const int n = n0 + 16 * a + (lane >> 4) * 4;
+    if (n >= p.N) continue;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int m = t * 16 + (lane & 15);
+      if (m >= p.M) continue;
+      floatx4 v = red[((0 * NT + a) * 4 + t) * 64 + lane];
+#pragma unroll
+      for (int w2 = 1; w2 < 4; ++w2) v += red[((w2 * NT + a) * 4 + t) * 64 + lane];
+      float v0 = v[0], v1 = v[1], v2 = v[2], v3 = v[3];
+      if (p.bias) {
+        const u32x2 bb = *reinterpret_cast<const u32x2*>(p.bias + n);
+        v0 += bf16_lo(bb[0]); v1 += bf16_hi(bb[0]);
+        v2 += bf16_lo(bb[1]); v3 += bf16_hi(bb[1]);
+      }
+      if (p.relu) {
+        v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f);
+        v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f);
+      }
+      if (p.residual) {
+        const u32x2 rr = *reinterpret_cast<const u32x2*>(p.residual + (size_t)m * p.N + n);
+        v0 += bf16_lo(rr[0]); v1 += bf16_hi(rr[0]);
+        v2 += bf16_lo(rr[1]); v3 += bf16_hi(rr[1]);
+      }
+      u32x2 ov;
+      ov[0] = pack_bf16(v0, v1);
+      ov[1] = pack_bf16(v2, v3);
+      const int hq = p.kv_n_heads * p.kv_head_dim, hkv = p.kv_n_kv_heads * p.kv_head_dim;
+      if (p.kv_k_cache && n >= hq) {  // decode QKV projection: this step's K / V row goes straight into its page
+        const int which = n >= hq + hkv;
+        const int col = n - hq - which * hkv;
+        const int head = col / p.kv_head_dim, d = col - head * p.kv_head_dim;
+        const int pos = p.kv_ctx_lens[m];
+        const int blk = p.kv_block_tables[(size_t)m * p.kv_max_blocks + pos / 16];
+        uint16_t* dst = (which ? p.kv_v_cache : p.kv_k_cache) +
+                        (((size_t)blk * p.kv_n_kv_heads + head) * 16 + (pos % 16)) * p.kv_head_dim + d;
+        *reinterpret_cast<u32x2*>(dst) = ov;
+        continue;
+      }
+      const int seg = (n >= p.seg_cols) + (n >= p.seg_cols + p.seg_cols_kv);
+      const int ld = seg == 0 ? p.seg_cols : p.seg_cols_kv;
+      const int first = seg == 0 ? 0 : p.seg_cols + (seg - 1) * p.seg_cols_kv;
       *reinterpret_cast<u32x2*>(p.out[seg] + (size_t)m * ld + (n - first)) = ov;
     }
   }
@@ -505,7 +658,7 @@ static SkinnyPlan skinny_plan(int M, int N, int K, bool allow_split = true) {
 
 size_t skinny_workspace_bytes(int M, int N, int K) {
   if (K % kSkKS != 0 || M > 256) return 0;
-  const SkinnyPlan pl = skinny_plan(M, N, K);
+  const SkinnyPlan pl = skinny_plan(M, N, K);  // (also covers the shapes the unsplit kernel takes)
   return pl.splits > 1 ? (size_t)pl.splits * M * N * sizeof(float) : 0;
 }
 
@@ -526,6 +679,35 @@ static hipError_t launch_skinny_cfg(const SkinnyParams& p, int splits, hipStream
   }
   hipLaunchKernelGGL(kern, dim3((p.N + BN - 1) / BN, splits), dim3(kSkThreads), lds_bytes, stream, p);
   return hipGetLastError();
+}
+
+template <int NT>
+static hipError_t launch_wring_cfg(const SkinnyParams& p, hipStream_t stream) {
+  constexpr size_t lds_bytes = (size_t)4 * 2 * (64 + 16 * NT) * kWrKS * sizeof(uint16_t);  // 4 waves x 2 stages
+  static_assert(lds_bytes <= 160 * 1024 && (size_t)NT * 16 * 1024 <= lds_bytes, "LDS");
+  auto kern = wring_gemm_kernel<NT>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((p.N + 16 * NT - 1) / (16 * NT)), dim3(kWrThreads), lds_bytes, stream, p);
+  return hipGetLastError();
+}
+
+// Column-tile width (in 16-row tiles) for the wave-private-ring kernel, or 0 if the shape is not one it
+// is good at: up to 64 rows, K a multiple of 256, and enough column tiles to occupy most of the chip
+// without splitting K.
+int g_skinny_wring = 1;  // development switch: 0 = never use the wave-private-ring kernel
+static int wring_tiles(int M, int N, int K) {
+  if (!g_skinny_wring || M > 64 || K < 256 || K % 256 != 0) return 0;
+  const int t4 = (N + 63) / 64, t5 = (N + 79) / 80;
+  const int r4 = (t4 + 255) / 256, r5 = (t5 + 255) / 256;
+  const int nt = r5 < r4 ? 5 : 4;
+  const int tiles = nt == 5 ? t5 : t4;
+  return tiles >= 160 ? nt : 0;
 }
 
 static hipError_t dispatch_skinny(const SkinnyParams& p, const SkinnyPlan& pl, hipStream_t stream) {
@@ -636,6 +818,22 @@ hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K,
   p.seg_cols_kv = ep.seg_cols_kv > 0 ? ep.seg_cols_kv : ep.seg_cols;
   p.M = M; p.N = N; p.K = K;
   p.relu = ep.relu;
+  // wide N, few rows: unsplit, wave-private rings, K/V scatter in its own epilogue
+  const bool plain = !fused || fused->kind == SkinnyFused::kNone;
+  const bool want_kv = fused && fused->kind == SkinnyFused::kKvAppend && ep.seg_cols == N && !ep.relu &&
+                       !ep.residual && N == (fused->n_heads + 2 * fused->n_kv_heads) * fused->head_dim &&
+                       fused->head_dim % 4 == 0;
+  const int nt = (plain || want_kv) ? wring_tiles(M, N, K) : 0;
+  if (nt > 0) {
+    if (want_kv) {
+      p.kv_ctx_lens = fused->ctx_lens; p.kv_block_tables = fused->block_tables; p.kv_max_blocks = fused->max_blocks;
+      p.kv_k_cache = (uint16_t*)fused->k_cache; p.kv_v_cache = (uint16_t*)fused->v_cache;
+      p.kv_n_heads = fused->n_heads; p.kv_n_kv_heads = fused->n_kv_heads; p.kv_head_dim = fused->head_dim;
+      if (fused_done) *fused_done = true;
+    }
+    p.partial = nullptr;
+    return nt == 5 ? launch_wring_cfg<5>(p, stream) : launch_wring_cfg<4>(p, stream);
+  }
   const SkinnyPlan pl = skinny_plan(M, N, K);
   p.partial = (float*)workspace;
   if (pl.splits > 1 && workspace == nullptr) return hipErrorInvalidValue;
