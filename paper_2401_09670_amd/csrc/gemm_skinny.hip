@@ -644,8 +644,11 @@ static SkinnyPlan skinny_plan(int M, int N, int K, bool allow_split = true) {
       if (wgs > 256.0 && splits > 1 && !forced) break;        // never split into a second round
       const double rounds = wgs <= 256.0 ? 1.0 : wgs / 256.0;  // unsplit but larger than the chip
       const double fill = wgs >= 256.0 ? 1.0 : 256.0 / wgs;    // idle CUs stretch the time
+      // partial sums are charged four times their bytes: they are stored by every workgroup at once at
+      // the end of the launch and read back by a second, latency-bound launch (measured: 6 splits of
+      // 128 columns beat 12 splits of 256 on the FFN-out shape although they stream more activations)
       const double bytes = 2.0 * N * K + 2.0 * wgs_n * (double)mp * K +
-                           (splits > 1 ? 2.0 * 4.0 * splits * (double)M * N : 0.0);
+                           (splits > 1 ? 4.0 * 2.0 * 4.0 * splits * (double)M * N : 0.0);
       const double cost = bytes * fill * rounds;
       if (cost < best_cost) {
         best_cost = cost;
