@@ -140,10 +140,11 @@ ds_status ds_layernorm(ds_ctx *ctx, const void *x, const void *gamma, const void
 
 /* y[rows,out_f] = act(x[rows,in_f] w[out_f,in_f]^T + bias) + residual   (GEMM tables
  * of App. A.2 / A.3).  bias, residual may be NULL; relu != 0 applies max(0,.)
- * before the residual.  in_f % 64 == 0, out_f % 8 == 0.  Rows <= 256 take the
- * weight-streaming path of the decode phase and need `workspace` of
- * ds_linear_workspace_bytes(); larger row counts take the MFMA tile path and
- * ignore it. */
+ * before the residual.  in_f % 64 == 0, out_f % 8 == 0.  Few rows take the
+ * weight-streaming kernels of the decode phase, many the MFMA tile kernel; either
+ * may split the reduction over workgroups and then needs `workspace` of
+ * ds_linear_workspace_bytes(rows, ...) bytes for fp32 partial sums (0 = none
+ * needed for this shape). */
 size_t ds_linear_workspace_bytes(const ds_ctx *ctx, int32_t rows, int32_t in_f, int32_t out_f);
 ds_status ds_linear(ds_ctx *ctx, const void *x, const void *w, const void *bias,
                     const void *residual, int32_t relu, int32_t rows, int32_t in_f, int32_t out_f,
