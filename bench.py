@@ -181,8 +181,8 @@ def main():
         with open(tpath) as f:
             per = json.load(f)["per_launch"]
         traffic = {k: v["hbm_read_bytes"] + v["hbm_write_bytes"] for k, v in per.items()}
-        if "skinny_reduce" in per:   # the class timed as skinny_gemm includes its split-K reduce launch
-            traffic["skinny_gemm"] += per["skinny_reduce"]["hbm_read_bytes"] + per["skinny_reduce"]["hbm_write_bytes"]
+        if "decode_gemm_call" in per:   # the class timed as skinny_gemm = either streaming kernel + its reduce launch
+            traffic["skinny_gemm"] = per["decode_gemm_call"]["hbm_read_bytes"] + per["decode_gemm_call"]["hbm_write_bytes"]
     kernels = {}
     for name, (bound, amount, peak) in work.items():
         ms, cnt = prof[name]
