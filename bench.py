@@ -320,8 +320,9 @@ def main():
 
 
 def time_oracle(np, synth, shape, seed, wbits, ctx0, B_dec, lens):
-    """The oracle as it stands (numpy, fp32 variant = the 'plain fp32 CPU decoder layer'), timed on
-    one prompt's prefill + hand-off and 2 decode steps of the full decode batch."""
+    """The oracle as it stands (numpy, fp32 variant = the 'plain fp32 CPU decoder layer'), timed on a
+    bounded sample with the workload's own mix: 8 prefill batches (+ their hand-off) and 32 decode steps
+    of the full decode batch, i.e. one prefill batch per four decode steps as in the timed step."""
     from oracle import ds_oracle as orc
     try:
         from threadpoolctl import threadpool_info
@@ -331,31 +332,35 @@ def time_oracle(np, synth, shape, seed, wbits, ctx0, B_dec, lens):
     h, n = shape.hidden, shape.n_heads
     w = orc.weights_from_bits(wbits, np.float32)
     t = sum(lens)
-    x = orc.from_bf16_bits(synth.make_activations(t, h, seed, stream=100), np.float32)
-    dec_steps = 8
+    n_pre, dec_steps = 8, 32
     bt, nblk = synth.make_block_tables([ctx0 + dec_steps] * B_dec, shape.block_size, seed)
     kc = np.zeros((nblk, n, shape.block_size, shape.head_dim), dtype=np.float32)
     vc = np.zeros_like(kc)
-    t0 = time.perf_counter()
-    y, k, v = orc.layer_prefill(w, x, lens, n, shape.ln_eps)
-    t_prefill = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    orc.kv_migrate(k, v, lens, bt[:len(lens)], kc, vc)
-    t_migrate = time.perf_counter() - t0
-    for i in range(len(lens), B_dec, len(lens)):   # untimed: give the other sequences a cache too
+    t_prefill = t_migrate = 0.0
+    for i in range(n_pre):
+        x = orc.from_bf16_bits(synth.make_activations(t, h, seed, stream=100 + i), np.float32)
+        t0 = time.perf_counter()
+        y, k, v = orc.layer_prefill(w, x, lens, n, shape.ln_eps)
+        t_prefill += time.perf_counter() - t0
+        rows = slice((i * len(lens)) % B_dec, (i * len(lens)) % B_dec + len(lens))
+        t0 = time.perf_counter()
+        orc.kv_migrate(k, v, lens, bt[rows], kc, vc)
+        t_migrate += time.perf_counter() - t0
+    for i in range(n_pre * len(lens), B_dec, len(lens)):   # untimed: give the remaining sequences a cache too
         orc.kv_migrate(k, v, lens, bt[i:i + len(lens)], kc, vc)
     xd = orc.from_bf16_bits(synth.make_activations(dec_steps * B_dec, h, seed, stream=200), np.float32)
     t0 = time.perf_counter()
     for j in range(dec_steps):
         orc.layer_decode_cached(w, xd[j * B_dec:(j + 1) * B_dec], [ctx0 + j] * B_dec, bt, kc, vc, n, shape.ln_eps)
     t_decode = time.perf_counter() - t0
-    tokens = t + dec_steps * B_dec
+    tokens = n_pre * t + dec_steps * B_dec
     total = t_prefill + t_migrate + t_decode
     return {"value": round(tokens / total, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"numpy fp32 oracle: one prefill batch ({len(lens)} prompts x {ctx0} tokens) + its KV "
-                      f"hand-off + {dec_steps} decode steps at B={B_dec}, ctx {ctx0}..{ctx0 + dec_steps}",
-            "prefill_tok_per_s": round(t / t_prefill, 1), "decode_ms_per_step": round(t_decode / dec_steps * 1e3, 1),
-            "migrate_GB_per_s": round(2 * 2 * t * h * 4 / t_migrate / 1e9, 3), "seconds": round(total, 2)}
+            "sample": f"numpy fp32 oracle: {n_pre} prefill batches ({len(lens)} prompts x {ctx0} tokens each) + their "
+                      f"KV hand-off + {dec_steps} decode steps at B={B_dec}, ctx {ctx0}..{ctx0 + dec_steps}",
+            "prefill_tok_per_s": round(n_pre * t / t_prefill, 1),
+            "decode_ms_per_step": round(t_decode / dec_steps * 1e3, 1),
+            "migrate_GB_per_s": round(n_pre * 2 * 2 * t * h * 4 / t_migrate / 1e9, 3), "seconds": round(total, 2)}
 
 
 if __name__ == "__main__":
