@@ -274,3 +274,56 @@ def test_decode_equals_prefill_last_row_on_gpu(gpu):
     got_a = run_path(shape, wbits, xbits[:l], [l], 1, seed, [xbits[l:l + 1]])
     got_b = run_path(shape, wbits, xbits, [l + 1], 0, seed, [])
     assert gu.rel_err(got_a["decode"][0][0], got_b["y"][l]) < TOL
+
+
+# ------------------------------------------------------------------ HIP graph capture
+def test_decode_step_replays_identically_from_a_hip_graph(gpu):
+    """A serving loop replays the decode step from a captured graph.  The step allocates nothing,
+    never synchronises and records no memset, so a capture (after one eager warm-up that sets the
+    kernels' LDS attributes) must replay bit-identically: three replays, each after eager work of its own
+    that changes the inputs, compared with the eager result on the same inputs."""
+    shape = synth.ModelShape(hidden=1024, n_heads=8, head_dim=128, ffn=4096)
+    seed, B, ctx0 = 4711, 24, 70
+    ctx = gu.make_ctx(shape)
+    lw, keep = gu.weights_to_dev(synth.make_layer_weights(shape, seed))
+    bt, nblk = synth.make_block_tables([ctx0 + 8] * B, 16, seed)
+    bt_d = gu.i32_dev(bt)
+    kfill, vfill = synth.make_kv_fill(nblk * 16, shape, seed)
+    kc0 = gu.to_dev(kfill).view(nblk, 16, shape.n_heads, shape.head_dim).permute(0, 2, 1, 3).contiguous()
+    vc0 = gu.to_dev(vfill).view(nblk, 16, shape.n_heads, shape.head_dim).permute(0, 2, 1, 3).contiguous()
+    ws = gu.workspace(ctx.ds_decode_workspace_bytes(B, ctx0 + 8))
+    x = torch.empty(B, shape.hidden, dtype=torch.bfloat16, device="cuda")
+    lens = torch.empty(B, dtype=torch.int32, device="cuda")
+    kc, vc = kc0.clone(), vc0.clone()
+    y = torch.empty_like(x)
+
+    def step():
+        ctx.ds_decode_step(lw, x, lens, bt_d, B, bt.shape[1], ctx0 + 8, kc, vc, nblk, y, ws)
+
+    def eager(j):
+        x.copy_(gu.to_dev(synth.make_activations(B, shape.hidden, seed, stream=10 + j)))
+        lens.fill_(ctx0 + j)
+        kc.copy_(kc0)
+        vc.copy_(vc0)
+
+    eager(0)
+    step()                                  # warm-up outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for j in range(1, 4):
+        eager(j)
+        step()
+        torch.cuda.synchronize()
+        want_y, want_k, want_v = y.clone(), kc.clone(), vc.clone()
+        eager(j)                            # same inputs again, caches restored
+        y.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want_y), j
+        assert torch.equal(kc, want_k) and torch.equal(vc, want_v), j
