@@ -1,10 +1,11 @@
-// bf16 GEMM on the CDNA4 matrix cores for the prefill phase:
+// bf16 GEMM on the CDNA4 matrix cores for the prefill phase (and for decoding batches too wide for
+// the streaming kernels):
 //   Y[M,N] = act(X[M,K] W[N,K]^T + bias) + residual,  fp32 accumulate.
 // Both operands are K-contiguous, so a lane's 8-element MFMA fragment is one
 // 16-byte LDS read.  The tile is computed transposed (weight rows as the MFMA
 // row operand, activation rows as the column operand).
 //
-// Tile BM x BN (activation rows x weight rows: 256x160, 256x256 or 128x128), BK = 64,
+// Tile BM x BN (activation rows x weight rows: 256x160, 256x256, 128x128 or 64x128), BK = 64,
 // 256 threads = 4 waves (one per SIMD).  Operands go global -> LDS directly (no register
 // staging), three LDS buffers (two for the 256x256 tile), one barrier per k-tile; fragment reads and load issue are
 // interleaved with the MFMAs by hand (scheduling fences); the epilogue is

@@ -1,9 +1,18 @@
-// Decode-phase GEMM: Y[M,N] = act(X[M,K] W[N,K]^T + bias) + residual, M <= 256.
+// Decode-phase GEMM: Y[M,N] = act(X[M,K] W[N,K]^T + bias) + residual for a handful of rows
+// (the library routes M <= 128 here; the kernels accept up to 256).
 // The weights (N*K*2 bytes) are read once from HBM and dominate the traffic
-// (App. A.3: 4h^2 + 2hm elements per layer), so the kernel is organised
+// (App. A.3: 4h^2 + 2hm elements per layer), so the kernels are organised
 // around streaming W at HBM rate while the matrix cores do the M x ... work.
 //
-// What bounds it on this chip is the number of bytes a CU can pull through
+// Two streaming kernels live here, plus the second passes of split-K:
+//   * wring_gemm_kernel  - wave-private rings, no split of K over workgroups, no second launch;
+//     taken for M <= 64 when N alone yields enough workgroups (described at the kernel).
+//   * skinny_gemm_kernel - one ring per workgroup, K split over workgroups; everything else.
+//   * skinny_reduce*_kernel - add the split partials in a fixed order and apply the epilogue,
+//     optionally fused with the LayerNorm that follows or with the append to the paged KV cache;
+//     also used by the tile GEMM when it splits K.
+//
+// What bounds the ring kernel on this chip is the number of bytes a CU can pull through
 // its vector L1 per unit time, and the activation slabs count against that
 // budget although they come from L2.  A workgroup therefore covers BN = 64,
 // 128 or 256 weight rows (the X slab is fetched once per BN columns), and the
