@@ -119,10 +119,14 @@ __global__ __launch_bounds__(kDecThreads) void decode_attention_kernel(
     for (int j = 0; j < NL; ++j) {
       const float p = exp2f(sc[j] * scale_log2e - mb);
       l_run += p;
+      // Slots past the sequence's end hold whatever the pool's memory held before (possibly NaN or Inf bit
+      // patterns): their weight is 0, but 0 * NaN is NaN, so their V bits are cleared as well.
+      const uint32_t keep = (pg * kDecPage + j * TPL + tg < kv_len) ? 0xffffffffu : 0u;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        acc[2 * e] += p * bf16_lo(vr[j][e]);
-        acc[2 * e + 1] += p * bf16_hi(vr[j][e]);
+        const uint32_t v2 = vr[j][e] & keep;
+        acc[2 * e] += p * bf16_lo(v2);
+        acc[2 * e + 1] += p * bf16_hi(v2);
       }
     }
     m_run = m_new;

@@ -103,6 +103,7 @@ struct Carver {
 // split over K where its tiles alone would not fill the chip (287 against 364 us at 256 rows).
 // Decode-sized calls (<= 256 rows) are timed as their own class whichever kernel runs.
 constexpr int kStreamMaxRows = 128;
+constexpr int kRowPad = 64;  // elements of padding per row of a padded internal buffer (128 bytes)
 bool use_skinny(int rows, int in_f) { return rows <= kStreamMaxRows && in_f % 128 == 0; }
 
 ds_status linear(ds_ctx* ctx, const void* x, const void* w, int rows, int in_f, int out_f,
@@ -202,8 +203,8 @@ size_t ds_prefill_workspace_bytes(const ds_ctx* ctx, int32_t max_tokens) {
   if (!ctx || max_tokens <= 0) return 0;
   const ds_model_cfg& c = ctx->cfg;
   const size_t th = align_up((size_t)max_tokens * c.hidden * 2, 256);
-  const size_t tm = align_up((size_t)max_tokens * c.ffn * 2, 256);
-  // a (LN out, reused for LN2), q, o, x1, u, + split-K partials of the GEMMs
+  const size_t tm = align_up((size_t)max_tokens * (c.ffn + kRowPad) * 2, 256);
+  // a (LN out, reused for LN2), q, o, x1, u (rows padded), + split-K partials of the GEMMs
   return 4 * th + tm + align_up(max_gemm_ws(c, max_tokens), 256);
 }
 
@@ -345,7 +346,13 @@ ds_status ds_prefill(ds_ctx* ctx, const ds_layer_weights* w, const void* x, cons
   void* q = ws.take((size_t)t * h * 2);
   void* o = ws.take((size_t)t * h * 2);
   void* x1 = ws.take((size_t)t * h * 2);
-  void* u = ws.take((size_t)t * m * 2);
+  // The FFN intermediate is written by one tile GEMM and read by the next: give its rows 128 bytes of
+  // padding so that consecutive rows do not start on the same memory channels (m * 2 bytes is a multiple of
+  // 8 KB for every OPT size; at OPT-175B's 96 KB the dense stride costs the second GEMM a quarter of its rate).
+  const bool pad_u = !use_skinny(t, h) && !use_skinny(t, m) && ds::gemm_splits(t, m, h) == 1 &&
+                     ds::gemm_splits(t, h, m) == 1;
+  const int ld_u = pad_u ? m + kRowPad : m;
+  void* u = ws.take((size_t)t * (m + kRowPad) * 2);
   void* sk = ws.take(0);
 
   // a = LN1(x)
@@ -379,6 +386,7 @@ ds_status ds_prefill(ds_ctx* ctx, const ds_layer_weights* w, const void* x, cons
     ds::Epilogue ep;
     ep.bias = w->b_fc1; ep.relu = 1;
     ep.out[0] = u; ep.seg_cols = m;
+    if (pad_u) ep.out_ld = ld_u;
     st = linear(ctx, a, w->w_fc1, t, h, m, ep, sk, s);
     if (st != DS_OK) return st;
   }
@@ -387,6 +395,7 @@ ds_status ds_prefill(ds_ctx* ctx, const ds_layer_weights* w, const void* x, cons
     ds::Epilogue ep;
     ep.bias = w->b_fc2; ep.residual = x1;
     ep.out[0] = y; ep.seg_cols = h;
+    if (pad_u) ep.x_ld = ld_u;
     st = linear(ctx, u, w->w_fc2, t, m, h, ep, sk, s);
     if (st != DS_OK) return st;
   }

@@ -30,6 +30,8 @@ struct GemmParams {
   int M, N, K;
   int relu;
   int tiles_m, tiles_n;
+  int ldx;     // row stride of X in elements (>= K)
+  int ld_out;  // row stride of out[0]
   // Split-K (gridDim.y = S > 1): split s multiplies k-tiles s, s + S, ... and stores its fp32
   // accumulators to partial[s][M][N]; the epilogue then belongs to whoever adds the partials.
   float* partial;
@@ -43,14 +45,31 @@ struct GemmParams {
   int n_heads, n_kv_heads, head_dim;
 };
 
-// Workgroup ids are dealt round-robin to the 8 XCDs (each with a private L2).
-// Give every XCD a contiguous range of tile ids, m-fastest, so the workgroups
-// that share an L2 also share weight tiles.
-__device__ __forceinline__ int xcd_remap(int pid, int total) {
-  constexpr int kXcd = 8;
-  const int per = total / kXcd;
-  if (pid >= per * kXcd) return pid;  // tail that does not fill all XCDs
-  return (pid % kXcd) * per + pid / kXcd;
+// Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs (each with a private L2).  With one
+// contiguous m-fastest range of tiles per XCD and many row tiles (long prefill batches), the 32 workgroups an
+// XCD runs at a time share one weight tile and read 32 different activation tiles, and the eight XCDs sit in
+// far-apart parts of the output, so every column tile re-streams the whole activation matrix from HBM.
+// Instead, the 256 workgroups that run together (32 per XCD, ids dealt round-robin) take one patch of up to
+// 16 x 16 output tiles, and inside it every XCD a 16 x 2 strip: 16 + 16 operand tiles from HBM per 256
+// output tiles, 16 + 2 through each L2 per 32.
+__device__ __forceinline__ void patch_tile(int pid, int tiles_m, int tiles_n, int& tm, int& tn) {
+  constexpr int kXcd = 8, kPerXcd = 32, kChunk = kXcd * kPerXcd, kGroupM = 16;
+  const int total = tiles_m * tiles_n;
+  const int full = total / kChunk * kChunk;
+  int v = pid;
+  if (pid < full) {
+    const int xcd = pid % kXcd, slot = pid / kXcd;
+    v = slot / kPerXcd * kChunk + xcd * kPerXcd + slot % kPerXcd;
+  } else {
+    const int per = (total - full) / kXcd, q = pid - full;  // last, partial chunk: equal contiguous shares
+    if (q < per * kXcd) v = full + (q % kXcd) * per + q / kXcd;
+  }
+  const int per_group = kGroupM * tiles_n;
+  const int g = v / per_group;
+  const int gsz = min(kGroupM, tiles_m - g * kGroupM);
+  const int r = v - g * per_group;
+  tm = g * kGroupM + r % gsz;
+  tn = r / gsz;
 }
 
 // ---------------------------------------------------------------------------
@@ -95,9 +114,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   const int wave = tid >> 6;
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
 
-  const int tile = xcd_remap(blockIdx.x, p.tiles_m * p.tiles_n);
-  const int m0 = (tile % p.tiles_m) * BM;
-  const int n0 = (tile / p.tiles_m) * BN;
+  int tile_m, tile_n;
+  patch_tile(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * BN;
   const int K = p.K;
   // Split-K deals the k-tiles round-robin (split s takes tiles s, s + S, ...), as the weight-streaming
   // kernel does: the splits of one output tile read neighbouring 128-byte pieces of the same rows at
@@ -113,7 +133,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
 #pragma unroll
   for (int j = 0; j < XL; ++j) {
     const int row = min(m0 + 8 * (4 * j + wave) + lrow, p.M - 1);
-    xoff[j] = (uint32_t)row * (uint32_t)K + lchunk * 8;
+    xoff[j] = (uint32_t)row * (uint32_t)p.ldx + lchunk * 8;
   }
 #pragma unroll
   for (int j = 0; j < WL; ++j) {
@@ -363,7 +383,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
           st16((which ? p.v_cache : p.k_cache) + (((size_t)blk * p.n_kv_heads + head) * 16 + (pos % 16)) * p.head_dim + d, o);
         } else {
           const int seg = (n >= p.seg_cols) + (n >= p.seg_cols + p.seg_cols_kv);
-          const int ld = seg == 0 ? p.seg_cols : p.seg_cols_kv;
+          const int ld = seg == 0 ? p.ld_out : p.seg_cols_kv;
           const int first = seg == 0 ? 0 : p.seg_cols + (seg - 1) * p.seg_cols_kv;
           st16(p.out[seg] + (size_t)row * ld + (n - first), o);
         }
@@ -448,6 +468,11 @@ static GemmPlan gemm_plan(int M, int N, int K) {
   return pl;
 }
 
+int gemm_splits(int M, int N, int K) {
+  if (M <= 0 || N <= 0 || K < kBK || K % kBK != 0) return 1;
+  return gemm_plan(M, N, K).splits;
+}
+
 // Bytes of split-K partials a launch with exactly M rows needs.
 size_t gemm_workspace_bytes(int M, int N, int K) {
   if (M <= 0 || N <= 0 || K < kBK || K % kBK != 0) return 0;
@@ -463,6 +488,11 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
       ep.seg_cols_kv % 8 != 0)
     return hipErrorInvalidValue;
   if (ep.residual && ep.seg_cols != N) return hipErrorInvalidValue;
+  if (ep.x_ld != 0 && (ep.x_ld < K || ep.x_ld % 8 != 0)) return hipErrorInvalidValue;
+  if (ep.out_ld != 0 && (ep.out_ld < N || ep.out_ld % 8 != 0 || ep.seg_cols != N)) return hipErrorInvalidValue;
+  // operand offsets inside the kernel are 32-bit element counts
+  if ((unsigned long long)M * (ep.x_ld > 0 ? ep.x_ld : K) >= (1ull << 32) || (unsigned long long)N * K >= (1ull << 32))
+    return hipErrorInvalidValue;
   GemmParams p;
   p.X = (const uint16_t*)X;
   p.W = (const uint16_t*)W;
@@ -471,6 +501,8 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
   for (int i = 0; i < 3; ++i) p.out[i] = (uint16_t*)ep.out[i];
   p.seg_cols = ep.seg_cols;
   p.seg_cols_kv = ep.seg_cols_kv > 0 ? ep.seg_cols_kv : ep.seg_cols;
+  p.ldx = ep.x_ld > 0 ? ep.x_ld : K;
+  p.ld_out = ep.out_ld > 0 ? ep.out_ld : ep.seg_cols;
   p.M = M; p.N = N; p.K = K;
   p.relu = ep.relu;
   p.tiles_m = p.tiles_n = 0;
@@ -479,6 +511,7 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
   p.k_cache = nullptr; p.v_cache = nullptr; p.n_heads = 0; p.n_kv_heads = 0; p.head_dim = 0;
   GemmPlan pl = gemm_plan(M, N, K);
   if (pl.splits > 1 && workspace == nullptr) pl.splits = 1;  // no room for partials: slower, still right
+  if (pl.splits > 1 && ep.out_ld != 0) return hipErrorInvalidValue;  // the reduce pass writes dense rows
   const bool want_kv = fused && fused->kind == SkinnyFused::kKvAppend && ep.seg_cols == N && !ep.relu &&
                        !ep.residual && N == (fused->n_heads + 2 * fused->n_kv_heads) * fused->head_dim &&
                        fused->head_dim % 8 == 0;

@@ -820,6 +820,7 @@ hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K,
       ep.seg_cols_kv % 8 != 0)
     return hipErrorInvalidValue;
   if (ep.residual && ep.seg_cols != N) return hipErrorInvalidValue;
+  if (ep.x_ld != 0 || ep.out_ld != 0) return hipErrorInvalidValue;  // dense rows only
   SkinnyParams p;
   p.X = (const uint16_t*)X;
   p.W = (const uint16_t*)W;

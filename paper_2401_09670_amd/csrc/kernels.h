@@ -25,6 +25,11 @@ struct Epilogue {
   void* out[3] = {nullptr, nullptr, nullptr};
   int seg_cols = 0;     // width (= row stride) of out[0]
   int seg_cols_kv = 0;  // width (= row stride) of out[1] and out[2]; 0 = seg_cols
+  // Row strides other than the dense ones, in elements (multiples of 8), for the MFMA tile kernel without
+  // split-K only: a row stride with many trailing zero bits (a 96 KB stride, say) lands the 128-byte pieces
+  // a tile reads from consecutive rows on few memory channels, so internal buffers get 128 bytes of padding.
+  int x_ld = 0;    // of X; 0 = K
+  int out_ld = 0;  // of out[0], single segment only; 0 = seg_cols
 };
 
 struct SkinnyFused;
@@ -34,6 +39,7 @@ struct SkinnyFused;
 // partials in `workspace` (gemm_workspace_bytes) and a second pass that also carries the epilogue.
 // `fused` asks for extra work (see SkinnyFused); *fused_done tells whether it was carried out.
 size_t gemm_workspace_bytes(int M, int N, int K);
+int gemm_splits(int M, int N, int K);  // 1 = the launch will not split K
 hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
                        hipStream_t stream, void* workspace = nullptr, const SkinnyFused* fused = nullptr,
                        bool* fused_done = nullptr);

@@ -91,6 +91,9 @@ def _linear_case(ctx, rows, in_f, out_f, bias, relu, residual, seed):
     (200, 5120, 5120, True, False, True),     # decode-sized rows on the tile kernel: split over K + reduce pass
     (129, 2048, 256, True, True, False),      # very few tiles: many splits
     (256, 4096, 1032, False, False, False),   # split-K with a ragged last column tile
+    (4400, 64, 4000, True, True, False),      # 18 x 16 tiles: a ragged last group of row tiles and a tile count
+                                              # that is no multiple of the 256 tiles dealt out together
+    (8200, 64, 1296, False, False, True),     # 33 row tiles: two full groups of 16 and a group of one
 ])
 def test_linear_tile_path(gpu, rows, in_f, out_f, bias, relu, residual):
     ctx = gu.make_ctx(synth.TINY)
@@ -149,8 +152,10 @@ def test_decode_attention(gpu, head_dim, n_heads, kv_lens):
     B, h = len(kv_lens), shape.hidden
     bt, nblk = synth.make_block_tables(kv_lens, 16, seed=41)
     kf, vf = synth.make_kv_fill(sum(kv_lens), shape, seed=42)
-    kc = np.zeros((nblk, n_heads, 16, head_dim), dtype=np.uint16)
-    vc = np.zeros_like(kc)
+    # slots no sequence owns (the tail of a last page, spare pages) hold what a pool's memory may hold after
+    # earlier use: NaN and -Inf bit patterns.  Their attention weight is 0, and they must not leak (0 * NaN)
+    kc = np.full((nblk, n_heads, 16, head_dim), 0x7FC0, dtype=np.uint16)
+    vc = np.full_like(kc, 0xFF80)
     orc.kv_migrate(kf, vf, kv_lens, bt, kc, vc)       # cache contents are an input here
     qb = synth.make_activations(B, h, seed=43)
     o = torch.zeros(B, h, dtype=torch.bfloat16, device="cuda")
@@ -182,8 +187,10 @@ def run_path(shape, wbits, xbits, lens, steps, seed, decode_x):
     ws = gu.workspace(ctx.ds_prefill_workspace_bytes(t))
     ctx.ds_prefill(lw, x, cu, B, t, max(lens), y, k_out, v_out, ws)
     bt, nblk = synth.make_block_tables([l + steps for l in lens], shape.block_size, seed)
-    kc = torch.zeros(nblk, shape.n_heads, 16, shape.head_dim, dtype=torch.bfloat16, device="cuda")
-    vc = torch.zeros_like(kc)
+    # the pool starts out as used memory may look (NaN / -Inf everywhere): only slots the path itself has
+    # written may ever influence a result
+    kc = torch.full((nblk, shape.n_heads, 16, shape.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    vc = torch.full_like(kc, float("-inf"))
     bt_d = gu.i32_dev(bt)
     ctx.ds_kv_migrate(k_out, v_out, cu, B, t, max(lens), bt_d, bt.shape[1], kc, vc, nblk)
     ctx_lens = np.array(lens, dtype=np.int32)
