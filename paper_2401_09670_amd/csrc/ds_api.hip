@@ -214,7 +214,13 @@ size_t ds_decode_workspace_bytes(const ds_ctx* ctx, int32_t max_batch, int32_t m
   const size_t bh = align_up((size_t)max_batch * c.hidden * 2, 256);
   const size_t b3h = align_up((size_t)max_batch * qkv_width(c) * 2, 256);
   const size_t bm = align_up((size_t)max_batch * c.ffn * 2, 256);
-  const size_t att = align_up(ds::decode_attention_workspace_bytes(max_batch, c.n_heads, c.head_dim, max_ctx), 256);
+  // fewer sequences can mean more splits of the KV axis: size the partials for any batch up to max_batch
+  size_t att = 0;
+  for (int b = 1; b <= max_batch; ++b) {
+    const size_t v = ds::decode_attention_workspace_bytes(b, c.n_heads, c.n_kv_heads, c.head_dim, max_ctx);
+    if (v > att) att = v;
+  }
+  att = align_up(att, 256);
   const size_t sk = align_up(max_gemm_ws(c, max_batch), 256);
   // a, qkv, o, x1, u, attention partials, split-K partials
   return 3 * bh + b3h + bm + att + sk;
@@ -436,7 +442,7 @@ ds_status ds_decode_attention(ds_ctx* ctx, const void* q, const int32_t* kv_lens
   if (!aligned16(q) || !aligned16(o) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(workspace))
     return fail(ctx, DS_ERR_INVALID_ARG, "ds_decode_attention: pointers must be 16-byte aligned");
   const ds_model_cfg& c = ctx->cfg;
-  const size_t need = ds::decode_attention_workspace_bytes(B, c.n_heads, c.head_dim, max_kv_len);
+  const size_t need = ds::decode_attention_workspace_bytes(B, c.n_heads, c.n_kv_heads, c.head_dim, max_kv_len);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(ctx, DS_ERR_WORKSPACE, "ds_decode_attention: workspace %zu < %zu", workspace_bytes, need);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -477,7 +483,7 @@ ds_status ds_decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, 
   const int hkv = kv_width(c), wqkv = qkv_width(c);
   void* qkv = ws.take((size_t)B * wqkv * 2);
   void* u = ws.take((size_t)B * m * 2);
-  void* att = ws.take(ds::decode_attention_workspace_bytes(B, c.n_heads, c.head_dim, max_ctx));
+  void* att = ws.take(ds::decode_attention_workspace_bytes(B, c.n_heads, c.n_kv_heads, c.head_dim, max_ctx));
   void* sk = ws.take(0);
 
   DS_LAUNCH(ctx, s, DS_K_LAYERNORM, ds::launch_layernorm(x, w->ln1_g, w->ln1_b, a, B, h, c.ln_eps, s));

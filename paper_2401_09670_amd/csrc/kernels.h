@@ -105,8 +105,8 @@ hipError_t launch_kv_append(const void* k_new, const void* v_new, int src_stride
 
 // One query per (sequence, head) over the paged cache.  kv_len_add is added to
 // kv_lens[i] (1 when kv_lens holds the lengths before this step's append).
-size_t decode_attention_workspace_bytes(int B, int n_heads, int head_dim, int max_kv_len);
-int decode_attention_splits(int B, int n_heads, int max_kv_len);
+size_t decode_attention_workspace_bytes(int B, int n_heads, int n_kv_heads, int head_dim, int max_kv_len);
+int decode_attention_splits(int B, int n_heads, int n_kv_heads, int head_dim, int max_kv_len);
 hipError_t launch_decode_attention(const void* q, int q_stride, const int32_t* kv_lens, int kv_len_add,
                                    const int32_t* block_tables, int B, int max_blocks, int max_kv_len,
                                    const void* k_cache, const void* v_cache, int n_heads, int n_kv_heads,

@@ -173,6 +173,47 @@ def test_decode_attention(gpu, head_dim, n_heads, kv_lens):
     assert gu.rel_err(gu.to_f64(o).reshape(B, n_heads, head_dim), ref) < TOL
 
 
+@pytest.mark.parametrize("n_heads,n_kv,kv_lens", [
+    (8, 4, [1, 16, 17, 33, 100, 600]),        # 2 query heads per key/value head; odd and even page counts
+    (8, 2, [512, 513, 31, 2, 48]),            # 4 per group
+    (16, 2, [3000]),                          # 8 per group, one sequence: KV axis split over workgroups
+    (10, 2, [2047, 5, 129]),                  # 5 per group (not a power of two): padded head columns stay out
+    (16, 1, [300, 40]),                       # 16 per group = a full tile of heads
+    (6, 1, [777]),                            # splits with an odd number of pages per split
+])
+def test_decode_attention_grouped_query(gpu, n_heads, n_kv, kv_lens):
+    """Query head j reads key/value head j / (n / n_kv) (grouped-query attention, Sec. 3.2); head size 128 takes
+    the kernel that serves a whole group per pass over the pages."""
+    head_dim = 128
+    shape = synth.ModelShape(hidden=n_heads * head_dim, n_heads=n_heads, head_dim=head_dim, ffn=256,
+                             n_kv_heads=n_kv)
+    ctx = gu.make_ctx(shape)
+    B, h = len(kv_lens), shape.hidden
+    bt, nblk = synth.make_block_tables(kv_lens, 16, seed=51)
+    kf, vf = synth.make_kv_fill(sum(kv_lens), shape, seed=52)
+    kc = np.full((nblk, n_kv, 16, head_dim), 0x7FC0, dtype=np.uint16)     # unowned slots: NaN / -Inf
+    vc = np.full_like(kc, 0xFF80)
+    orc.kv_migrate(kf, vf, kv_lens, bt, kc, vc)
+    qb = synth.make_activations(B, h, seed=53)
+    o = torch.zeros(B, h, dtype=torch.bfloat16, device="cuda")
+    ws = gu.workspace(ctx.ds_decode_workspace_bytes(B, max(kv_lens)))
+    ctx.ds_decode_attention(gu.to_dev(qb), gu.i32_dev(kv_lens), gu.i32_dev(bt), B, bt.shape[1], max(kv_lens),
+                            gu.to_dev(kc), gu.to_dev(vc), nblk, o, ws)
+    torch.cuda.synchronize()
+    q = orc.from_bf16_bits(qb).reshape(B, n_heads, head_dim)
+    cu = synth.cu_seqlens(kv_lens)
+    ref = np.empty_like(q)
+    for i, l in enumerate(kv_lens):
+        ks = orc.from_bf16_bits(kf[cu[i]:cu[i] + l])
+        vs = orc.from_bf16_bits(vf[cu[i]:cu[i] + l])
+        ref[i] = orc.attention_rows(q[i:i + 1], np.array([l - 1]), ks, vs)[0]
+    got = gu.to_f64(o).reshape(B, n_heads, head_dim)
+    assert np.all(np.isfinite(got))
+    assert gu.rel_err(got, ref) < TOL
+    for i in range(B):                       # per sequence too: a short one must not hide behind a long one
+        assert gu.rel_err(got[i], ref[i]) < TOL, (i, kv_lens[i])
+
+
 # ------------------------------------------------------------------ whole path, config 1 (tiny), every element
 def run_path(shape, wbits, xbits, lens, steps, seed, decode_x):
     """prefill -> migrate -> `steps` decode steps on the GPU; returns device results as numpy."""
