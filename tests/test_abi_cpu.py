@@ -76,3 +76,22 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libds.so")
     with pytest.raises(RuntimeError):
         binding.Context(256, 4, 64, 1024)
+
+
+@pytest.mark.parametrize("hidden,n_heads,head_dim,ffn,n_kv", [
+    (256, 4, 64, 1024, 0), (5120, 40, 128, 20480, 0), (8192, 64, 128, 28672, 8), (2048, 16, 128, 4096, 1),
+])
+def test_workspace_for_a_maximum_serves_every_smaller_call(hidden, n_heads, head_dim, ffn, n_kv):
+    """A caller sizes one workspace for its largest batch; smaller batches may split K or the KV axis over
+    more workgroups (more partial sums), and must still fit."""
+    ctx = binding.Context(hidden, n_heads, head_dim, ffn, n_kv_heads=n_kv)
+    for max_batch, max_ctx in ((1, 16), (7, 300), (64, 4096), (256, 2048)):
+        cap = ctx.ds_decode_workspace_bytes(max_batch, max_ctx)
+        assert cap > 0
+        for b in sorted(b for b in {1, 2, 3, max_batch // 2, max_batch - 1, max_batch} if 1 <= b <= max_batch):
+            for c in (1, max_ctx // 3 or 1, max_ctx):
+                assert ctx.ds_decode_workspace_bytes(b, c) <= cap, (max_batch, max_ctx, b, c)
+    for max_tokens in (1, 100, 2048, 5000):
+        cap = ctx.ds_prefill_workspace_bytes(max_tokens)
+        for t in sorted({1, max_tokens // 2 or 1, max_tokens}):
+            assert ctx.ds_prefill_workspace_bytes(t) <= cap
