@@ -83,7 +83,9 @@ void ds_destroy(ds_ctx *ctx);
 /* Text of the last error recorded on ctx (never NULL). */
 const char *ds_last_error(const ds_ctx *ctx);
 
-/* Workspace (device bytes) ds_prefill needs for up to max_tokens packed tokens. */
+/* Workspace (device bytes) ds_prefill needs for up to max_tokens packed tokens.
+ * Both sizes are upper bounds over all smaller calls: a workspace sized for the
+ * largest batch serves every call with fewer tokens / sequences / cached tokens. */
 size_t ds_prefill_workspace_bytes(const ds_ctx *ctx, int32_t max_tokens);
 /* Workspace ds_decode_step needs for up to max_batch sequences of up to max_ctx cached tokens. */
 size_t ds_decode_workspace_bytes(const ds_ctx *ctx, int32_t max_batch, int32_t max_ctx);
@@ -124,6 +126,8 @@ ds_status ds_kv_migrate(ds_ctx *ctx, const void *k_src, const void *v_src,
  *            ctx_lens[i]+1 keys.  The caller increments ctx_lens between steps.
  *   max_ctx  host upper bound of ctx_lens[i]+1 (sizes the split of the KV axis)
  *   y        device [B,h] bf16; must not alias x
+ * Cache slots past a sequence's last token (the rest of its last page) may hold
+ * any bit pattern, NaN included: they never reach a result.
  */
 ds_status ds_decode_step(ds_ctx *ctx, const ds_layer_weights *w, const void *x,
                          const int32_t *ctx_lens, const int32_t *block_tables,
