@@ -32,6 +32,7 @@ struct GemmParams {
   int tiles_m, tiles_n;
   int ldx;     // row stride of X in elements (>= K)
   int ld_out;  // row stride of out[0]
+  int ld_res;  // row stride of residual
   // Split-K (gridDim.y = S > 1): split s multiplies k-tiles s, s + S, ... and stores its fp32
   // accumulators to partial[s][M][N]; the epilogue then belongs to whoever adds the partials.
   float* partial;
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
       resv[it] = u32x4{0, 0, 0, 0};
       biasv[it] = u32x4{0, 0, 0, 0};
       if (EPI == kEpiPartial) continue;
-      if (ok && p.residual) resv[it] = ld16(p.residual + (size_t)row * p.N + n);
+      if (ok && p.residual) resv[it] = ld16(p.residual + (size_t)row * p.ld_res + n);
       // when cpr divides 64 the chunk (hence the bias piece) is the same for every `it`
       if (ok && p.bias && (it == 0 || 64 % cpr != 0)) biasv[it] = ld16(p.bias + n);
     }
@@ -468,6 +469,31 @@ static GemmPlan gemm_plan(int M, int N, int K) {
   return pl;
 }
 
+// Tile quantisation: a launch takes whole rounds of 256 workgroups, so 2.5 rounds cost 3.  Where it pays, the
+// product is cut at a column: the leading n1 columns keep the large tile and fill their rounds (nearly)
+// completely, the remaining ones take 128x128 tiles, whose last round wastes a quarter as much.  Returns n1, or
+// 0 to leave the launch whole.  Costs in the units of tile_cost.
+int g_gemm_tail_split = 1;  // development switch (timing harness only)
+static int tail_split_columns(int M, int N, int variant) {
+  if (!g_gemm_tail_split || (variant != 1 && variant != 3)) return 0;
+  const int bm = 256, bn = variant == 1 ? 160 : 256;
+  const double big = bm * bn * (variant == 1 ? 1.0 : 0.9), small = 128 * 128 * 1.3;
+  const long tm = (M + bm - 1) / bm, tn = (N + bn - 1) / bn, tm2 = (M + 127) / 128;
+  const double whole = (double)((tm * tn + 255) / 256) * big;
+  double best = whole;
+  int best_c = 0;
+  for (long c = 1; c < tn; ++c) {
+    const long rest = N - c * bn;
+    if (rest <= 0) break;
+    const double cost = (double)((tm * c + 255) / 256) * big + (double)((tm2 * ((rest + 127) / 128) + 255) / 256) * small;
+    if (cost < best) {
+      best = cost;
+      best_c = (int)c;
+    }
+  }
+  return best < 0.95 * whole ? best_c * bn : 0;  // a second launch has to earn its ramp-up
+}
+
 int gemm_splits(int M, int N, int K) {
   if (M <= 0 || N <= 0 || K < kBK || K % kBK != 0) return 1;
   return gemm_plan(M, N, K).splits;
@@ -503,6 +529,7 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
   p.seg_cols_kv = ep.seg_cols_kv > 0 ? ep.seg_cols_kv : ep.seg_cols;
   p.ldx = ep.x_ld > 0 ? ep.x_ld : K;
   p.ld_out = ep.out_ld > 0 ? ep.out_ld : ep.seg_cols;
+  p.ld_res = N;
   p.M = M; p.N = N; p.K = K;
   p.relu = ep.relu;
   p.tiles_m = p.tiles_n = 0;
@@ -525,6 +552,24 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
     if (fused_done) *fused_done = true;
   }
   hipError_t e;
+  const int n1 = (pl.splits == 1 && !p.k_cache && ep.seg_cols == N) ? tail_split_columns(M, N, pl.variant) : 0;
+  if (n1 > 0) {
+    // Leading columns on the large tile in (nearly) whole rounds of 256 workgroups, the rest on 128x128 tiles:
+    // two launches over disjoint column ranges of the same product.
+    GemmParams a = p, b = p;
+    a.N = n1;
+    a.seg_cols = a.seg_cols_kv = n1;
+    b.W = p.W + (size_t)n1 * K;
+    b.bias = p.bias ? p.bias + n1 : nullptr;
+    b.residual = p.residual ? p.residual + n1 : nullptr;
+    b.out[0] = p.out[0] + n1;
+    b.N = N - n1;
+    b.seg_cols = b.seg_cols_kv = N - n1;
+    e = pl.variant == 3 ? launch_dl<256, 256, 2, 2, 2, false>(a, 1, stream)
+                        : launch_dl<256, 160, 4, 1, 3, false>(a, 1, stream);
+    if (e != hipSuccess) return e;
+    return launch_dl<128, 128, 2, 2, 3, true>(b, 1, stream);
+  }
   switch (pl.variant) {
     case 4: e = launch_dl<64, 128, 1, 4, 3, true>(p, pl.splits, stream); break;
     case 3: e = launch_dl<256, 256, 2, 2, 2, false>(p, pl.splits, stream); break;

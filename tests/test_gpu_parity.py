@@ -94,6 +94,8 @@ def _linear_case(ctx, rows, in_f, out_f, bias, relu, residual, seed):
     (4400, 64, 4000, True, True, False),      # 18 x 16 tiles: a ragged last group of row tiles and a tile count
                                               # that is no multiple of the 256 tiles dealt out together
     (8200, 64, 1296, False, False, True),     # 33 row tiles: two full groups of 16 and a group of one
+    (2048, 64, 20480, True, True, True),      # 2.5 rounds of large tiles: cut at a column, the tail on small tiles
+    (3738, 128, 9216, True, False, True),     # the same with ragged rows (bias and residual follow the cut)
 ])
 def test_linear_tile_path(gpu, rows, in_f, out_f, bias, relu, residual):
     ctx = gu.make_ctx(synth.TINY)
