@@ -61,8 +61,9 @@ def _check_decode_capture(stack, li, cap, sample, dtype):
         assert gu.rel_err(k_before[blk, :, slot].astype(np.float64), okc[blk, :, slot].astype(np.float64)) < TOL
 
 
-def test_small_stack_runs_a_workload_to_completion_with_layerwise_parity(gpu):
-    shape = synth.ModelShape(hidden=512, n_heads=4, head_dim=128, ffn=2048, n_layers=4)
+@pytest.mark.parametrize("n_kv", [0, 2])     # multi-head, and two query heads per key/value head
+def test_small_stack_runs_a_workload_to_completion_with_layerwise_parity(gpu, n_kv):
+    shape = synth.ModelShape(hidden=512, n_heads=4, head_dim=128, ffn=2048, n_layers=4, n_kv_heads=n_kv)
     L, vocab = 4, 1024
     rng = np.random.default_rng(11)
     reqs = [inst.Request(i, int(rng.integers(1, 150)), int(rng.integers(1, 24))) for i in range(24)]
