@@ -282,8 +282,8 @@ __global__ __launch_bounds__(kSkThreads) void skinny_gemm_kernel(const SkinnyPar
 // stall together - two independent 16 KB streams per CU reach 5.7 TB/s, one 64 KB stream 5.3.
 //
 // So: a workgroup (4 waves) owns 64 output columns over the whole K; its waves split K between them
-// 64-wide slab by slab (wave w takes slabs w, w+4, ...) and each wave runs its OWN two-stage
-// direct-to-LDS ring [64 activation rows | 64 weight rows] x 128 bytes, waiting on nothing but its
+// 64-wide slab by slab (wave w takes slabs w, w+4, ...) and each wave runs its OWN two- or three-stage
+// direct-to-LDS ring [16, 32 or 64 activation rows | 64 or 80 weight rows] x 128 bytes, waiting on nothing but its
 // own loads - no barrier in the loop, four desynchronised streams per CU.  The four waves' 64 x 64
 // fp32 tiles are added through LDS at the end (fixed order) and wave w finishes column tile w.
 // grid = N / 64 workgroups, no partial sums in global memory, no second launch.
@@ -292,12 +292,16 @@ constexpr int kWrThreads = 256;
 constexpr int kWrKS = 64;  // k elements per slab
 
 // NT = weight row tiles of 16 per workgroup (4 or 5: 64 or 80 output columns, whichever tiles N into
-// fewer rounds of 256 workgroups).
-template <int NT>
+// fewer rounds of 256 workgroups); MT = activation row tiles of 16 (1, 2 or 4: batches of up to 16, 32 or
+// 64 sequences - a small batch does not pay for 64 activation rows per slab: worth 2 us of a 158 us step at
+// OPT-13B, the rest of such a step is weight bytes and per-launch ramps); S = stages of a wave's ring (the
+// smaller stages of small batches leave room for a third: two slabs in flight per wave).
+template <int NT, int MT, int S>
 __global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyParams p) {
-  constexpr int kWrBN = 16 * NT;
-  constexpr int kWrStageElems = (64 + kWrBN) * kWrKS;  // [64 X rows | BN W rows] x 64 k
-  constexpr int kWrLoads = (64 + kWrBN) / 8;           // wave-level loads (8 rows x 128 B) per slab
+  constexpr int kWrBN = 16 * NT, kWrBM = 16 * MT;
+  constexpr int kWrStageElems = (kWrBM + kWrBN) * kWrKS;  // [BM X rows | BN W rows] x 64 k
+  constexpr int kWrLoads = (kWrBM + kWrBN) / 8;           // wave-level loads (8 rows x 128 B) per slab
+  static_assert((S - 1) * kWrLoads < 64, "vmcnt range");
   extern __shared__ __attribute__((aligned(1024))) uint16_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -306,17 +310,17 @@ __global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyPara
   const int slabs_total = K / kWrKS;
   const int ns = (slabs_total - wave + 3) / 4;  // this wave's slabs: wave, wave + 4, ...  (>= 1: K >= 256)
 
-  // load j of a slab covers stage rows 8j .. 8j+7 (rows 0..63 = X, 64..127 = W); lane: row 8j + lane/8,
+  // load j of a slab covers stage rows 8j .. 8j+7 (rows 0..BM-1 = X, then W); lane: row 8j + lane/8,
   // 16-byte chunk (lane%8) ^ ((row >> 1) & 7) - the swizzle that makes the fragment reads conflict-free
   const uint16_t* src[kWrLoads];
 #pragma unroll
   for (int j = 0; j < kWrLoads; ++j) {
     const int r = 8 * j + (lane >> 3);
     const int sw = ((lane & 7) ^ ((r >> 1) & 7)) * 8;
-    if (r < 64) src[j] = p.X + (size_t)min(r, p.M - 1) * K + (size_t)wave * kWrKS + sw;
-    else src[j] = p.W + (size_t)min(n0 + r - 64, p.N - 1) * K + (size_t)wave * kWrKS + sw;
+    if (r < kWrBM) src[j] = p.X + (size_t)min(r, p.M - 1) * K + (size_t)wave * kWrKS + sw;
+    else src[j] = p.W + (size_t)min(n0 + r - kWrBM, p.N - 1) * K + (size_t)wave * kWrKS + sw;
   }
-  uint16_t* ring = lds + wave * 2 * kWrStageElems;
+  uint16_t* ring = lds + wave * S * kWrStageElems;
   auto request = [&](int i, int st) {  // this wave's slab i (clamped: a harmless re-load) into its stage st
     const int ofs = min(i, ns - 1) * 4 * kWrKS;
     uint16_t* dst = ring + st * kWrStageElems;
@@ -326,37 +330,40 @@ __global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyPara
                                        (__attribute__((address_space(3))) void*)(dst + j * 512), 16, 0, 0);
   };
 
-  floatx4 acc[NT][4];  // [weight row tile a][activation row tile t]
+  floatx4 acc[NT][MT];  // [weight row tile a][activation row tile t]
 #pragma unroll
   for (int a = 0; a < NT; ++a)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc[a][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < MT; ++t) acc[a][t] = floatx4{0.f, 0.f, 0.f, 0.f};
   // fragment of k-step s (32 k): lane (row r = lane%16 of a 16-row tile, quarter q = lane/16) reads chunk 4s+q
   int fo[2];
 #pragma unroll
   for (int s2 = 0; s2 < 2; ++s2)
     fo[s2] = (lane & 15) * kWrKS + (((4 * s2 + (lane >> 4)) ^ (((lane & 15) >> 1) & 7)) * 8);
 
-  request(0, 0);
+#pragma unroll
+  for (int i = 0; i < S - 1; ++i) request(i, i);
+  int st = 0, st_in = S - 1;  // stage read in this iteration; stage the newest request goes into
   for (int i = 0; i < ns; ++i) {
-    const int st = i & 1;
-    request(i + 1, st ^ 1);          // the other stage was last read in iteration i-1
-    sk_wait_vmcnt<kWrLoads>();       // slab i has landed (slab i+1 may still fly)
+    request(i + S - 1, st_in);            // that stage was last read in iteration i-1
+    sk_wait_vmcnt<(S - 1) * kWrLoads>();  // slab i has landed (the S-1 younger ones may still fly)
     const uint16_t* sb = ring + st * kWrStageElems;
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
-      u32x4 xf[4];
+      u32x4 xf[MT];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) xf[t] = *reinterpret_cast<const u32x4*>(sb + t * 16 * kWrKS + fo[s2]);
+      for (int t = 0; t < MT; ++t) xf[t] = *reinterpret_cast<const u32x4*>(sb + t * 16 * kWrKS + fo[s2]);
 #pragma unroll
       for (int a = 0; a < NT; ++a) {
-        const u32x4 wf = *reinterpret_cast<const u32x4*>(sb + (64 + a * 16) * kWrKS + fo[s2]);
+        const u32x4 wf = *reinterpret_cast<const u32x4*>(sb + (kWrBM + a * 16) * kWrKS + fo[s2]);
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < MT; ++t)
           acc[a][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf),
                                                               __builtin_bit_cast(bf16x8, xf[t]), acc[a][t], 0, 0, 0);
       }
     }
+    st = st + 1 == S ? 0 : st + 1;
+    st_in = st_in + 1 == S ? 0 : st_in + 1;
   }
   sk_wait_vmcnt<0>();  // the clamped re-load of the last iteration must not land in the reduction area
   __syncthreads();     // every wave is done with its ring: reuse the LDS to add the four waves' tiles
@@ -365,7 +372,7 @@ __global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyPara
 #pragma unroll
     for (int a = 0; a < NT; ++a)
 #pragma unroll
-      for (int t = 0; t < 4; ++t) red[((wave * NT + a) * 4 + t) * 64 + lane] = acc[a][t];
+      for (int t = 0; t < MT; ++t) red[((wave * NT + a) * MT + t) * 64 + lane] = acc[a][t];
     __syncthreads();
   }
   // wave w finishes weight row tiles a = w (and w + 4): the four waves' tiles are added in wave order.
@@ -375,12 +382,12 @@ __global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyPara
     const int n = n0 + 16 * a + (lane >> 4) * 4;
     if (n >= p.N) continue;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < MT; ++t) {
       const int m = t * 16 + (lane & 15);
       if (m >= p.M) continue;
-      floatx4 v = red[((0 * NT + a) * 4 + t) * 64 + lane];
+      floatx4 v = red[((0 * NT + a) * MT + t) * 64 + lane];
 #pragma unroll
-      for (int w2 = 1; w2 < 4; ++w2) v += red[((w2 * NT + a) * 4 + t) * 64 + lane];
+      for (int w2 = 1; w2 < 4; ++w2) v += red[((w2 * NT + a) * MT + t) * 64 + lane];
       float v0 = v[0], v1 = v[1], v2 = v[2], v3 = v[3];
       if (p.bias) {
         const u32x2 bb = *reinterpret_cast<const u32x2*>(p.bias + n);
@@ -693,11 +700,11 @@ static hipError_t launch_skinny_cfg(const SkinnyParams& p, int splits, hipStream
   return hipGetLastError();
 }
 
-template <int NT>
+template <int NT, int MT, int S>
 static hipError_t launch_wring_cfg(const SkinnyParams& p, hipStream_t stream) {
-  constexpr size_t lds_bytes = (size_t)4 * 2 * (64 + 16 * NT) * kWrKS * sizeof(uint16_t);  // 4 waves x 2 stages
-  static_assert(lds_bytes <= 160 * 1024 && (size_t)NT * 16 * 1024 <= lds_bytes, "LDS");
-  auto kern = wring_gemm_kernel<NT>;
+  constexpr size_t lds_bytes = (size_t)4 * S * (16 * MT + 16 * NT) * kWrKS * sizeof(uint16_t);  // 4 waves x S stages
+  static_assert(lds_bytes <= 160 * 1024 && (size_t)4 * NT * MT * 1024 <= lds_bytes, "LDS");
+  auto kern = wring_gemm_kernel<NT, MT, S>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -707,6 +714,19 @@ static hipError_t launch_wring_cfg(const SkinnyParams& p, hipStream_t stream) {
   }
   hipLaunchKernelGGL(kern, dim3((p.N + 16 * NT - 1) / (16 * NT)), dim3(kWrThreads), lds_bytes, stream, p);
   return hipGetLastError();
+}
+
+// The instantiation for NT column tiles and the batch's row count.
+static hipError_t launch_wring(int nt, const SkinnyParams& p, hipStream_t stream) {
+  const int M = p.M;
+  if (nt == 5) {
+    if (M <= 16) return launch_wring_cfg<5, 1, 3>(p, stream);  // 144 KB
+    if (M <= 32) return launch_wring_cfg<5, 2, 2>(p, stream);  // 112 KB
+    return launch_wring_cfg<5, 4, 2>(p, stream);               // 144 KB
+  }
+  if (M <= 16) return launch_wring_cfg<4, 1, 3>(p, stream);    // 120 KB
+  if (M <= 32) return launch_wring_cfg<4, 2, 3>(p, stream);    // 144 KB
+  return launch_wring_cfg<4, 4, 2>(p, stream);                 // 128 KB
 }
 
 // Column-tile width (in 16-row tiles) for the wave-private-ring kernel, or 0 if the shape is not one it
@@ -845,7 +865,7 @@ hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K,
       if (fused_done) *fused_done = true;
     }
     p.partial = nullptr;
-    return nt == 5 ? launch_wring_cfg<5>(p, stream) : launch_wring_cfg<4>(p, stream);
+    return launch_wring(nt, p, stream);
   }
   const SkinnyPlan pl = skinny_plan(M, N, K);
   p.partial = (float*)workspace;

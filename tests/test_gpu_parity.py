@@ -110,6 +110,10 @@ def test_linear_tile_path(gpu, rows, in_f, out_f, bias, relu, residual):
     (100, 2048, 512, True, True, False),
     (256, 1024, 384, True, False, True),
     (33, 320, 256, True, False, False),       # in_f not a multiple of 128 -> tile path
+    # wide outputs, unsplit streaming kernel: one instantiation per batch size class (16 / 32 / 64 rows)
+    # and column-tile width (64 columns at 10240, 80 at 20480)
+    (1, 512, 10240, True, False, False), (16, 256, 20480, True, True, False), (17, 768, 10240, False, False, True),
+    (32, 512, 20480, True, False, True), (33, 256, 10240, True, True, False), (9, 1024, 20480, False, False, False),
 ])
 def test_linear_skinny_path(gpu, rows, in_f, out_f, bias, relu, residual):
     ctx = gu.make_ctx(synth.TINY)
