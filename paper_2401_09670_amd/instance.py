@@ -302,12 +302,11 @@ class GpuStack:
         self.da, self.db = torch.empty((self.max_batch, h), **bf), torch.empty((self.max_batch, h), **bf)
         self.ws_decode = torch.empty(max(self.ctx.ds_decode_workspace_bytes(self.max_batch, self.max_ctx), 256),
                                      dtype=torch.uint8, device=self.dev)
-        nt_rows = min(256, max(self.max_batch, 1))
         self.ws_next = torch.empty(max(self.ctx.ds_next_token_workspace_bytes(256, self.vocab), 256),
                                    dtype=torch.uint8, device=self.dev)
         self.cur_tok = torch.zeros(self.max_batch, dtype=torch.int32, device=self.dev)      # per decode row
         self.first_tok = torch.zeros(int(max_requests), dtype=torch.int32, device=self.dev)  # per request id
-        self.next_tok = torch.empty(max(256, nt_rows), dtype=torch.int32, device=self.dev)
+        self.next_tok = torch.empty(256, dtype=torch.int32, device=self.dev)   # ds_next_token takes <= 256 rows
         # Tests set this to {layer: []}: copies of those layers' inputs and outputs are appended per call
         # (for a decoding step also the layer's pool as the step leaves it).
         self.capture = None
