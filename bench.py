@@ -294,6 +294,34 @@ def main():
             "hbm_frac": round(bytes_t / (mst * 1e-3) / cost.PEAK_HBM_BYTES, 4)}
         del wv, xn
 
+        # Grouped-query decode attention (64 query heads on 8 key/value heads, the geometry of a 70B-class
+        # grouped-query model; OPT itself is multi-head): the kernel that serves a whole group per pass over
+        # the pages, priced by the K/V bytes it has to read once.
+        gn, gkv, gB, gctx = 64, 8, 64, 2048
+        gctx_ = binding.Context(gn * s, gn, s, 4 * gn * s, shape.block_size, shape.ln_eps, gkv)
+        gbt, gnblk = synth.make_block_tables([gctx] * gB, shape.block_size, seed + 9)
+        gk = torch.empty(gnblk, gkv, shape.block_size, s, dtype=torch.bfloat16, device=dev).normal_()
+        gv = torch.empty_like(gk).normal_()
+        gq = torch.empty(gB, gn * s, dtype=torch.bfloat16, device=dev).normal_()
+        go = torch.empty_like(gq)
+        glens = torch.full((gB,), gctx, dtype=torch.int32, device=dev)
+        gbt_d = torch.from_numpy(gbt).to(dev)
+        gws = torch.empty(max(gctx_.ds_decode_workspace_bytes(gB, gctx), 256), dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            gctx_.ds_decode_attention(gq, glens, gbt_d, gB, gbt.shape[1], gctx, gk, gv, gnblk, go, gws)
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(10):
+            gctx_.ds_decode_attention(gq, glens, gbt_d, gB, gbt.shape[1], gctx, gk, gv, gnblk, go, gws)
+        b.record()
+        torch.cuda.synchronize()
+        msa = a.elapsed_time(b) / 10
+        bytes_a = 2.0 * gB * gctx * gkv * s * 2
+        extras["decode_attn_gqa_n64_kv8_b64_ctx2048"] = {
+            "ms": round(msa, 4), "GB_per_s": round(bytes_a / (msa * 1e-3) / 1e9, 1),
+            "hbm_frac": round(bytes_a / (msa * 1e-3) / cost.PEAK_HBM_BYTES, 4)}
+        del gk, gv, gq, go
+
     # ---------------- CPU oracle on a bounded sample of the same workload ----------------
     cpu_baseline = None
     if not args.no_cpu_baseline:
