@@ -140,16 +140,38 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
     if (kv0 > qw0 + 31) continue;  // every key of this tile is in the future of this wave's queries
 
     // ---- S^T = K Q^T : two 32-key row tiles ----
+    // The two row tiles advance together, so that consecutive matrix instructions write different
+    // accumulators (a chain on one accumulator waits out the full latency of every instruction), and the K
+    // fragments are requested from LDS half a tile ahead of their use (scheduling fences keep the compiler
+    // from sinking each read down to its instruction, which exposes the LDS latency sixteen times).
     floatx16 sacc[2];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[u][r] = 0.f;
-      const uint16_t* kr = ks + (u * 32 + lq) * KS + hl * 8;
+    {
+      constexpr int HS = DSTEPS / 2;
+      const uint16_t* kr0 = ks + lq * KS + hl * 8;
+      const uint16_t* kr1 = kr0 + 32 * KS;
+      bf16x8 kf[2][HS];
 #pragma unroll
-      for (int st = 0; st < DSTEPS; ++st) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kr + st * 16);
-        sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sacc[u], 0, 0, 0);
+      for (int st = 0; st < HS; ++st) {
+        kf[0][st] = *reinterpret_cast<const bf16x8*>(kr0 + st * 16);
+        kf[1][st] = *reinterpret_cast<const bf16x8*>(kr1 + st * 16);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int st = 0; st < HS; ++st) {
+        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][st], qf[st], sacc[0], 0, 0, 0);
+        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][st], qf[st], sacc[1], 0, 0, 0);
+        kf[0][st] = *reinterpret_cast<const bf16x8*>(kr0 + (st + HS) * 16);
+        kf[1][st] = *reinterpret_cast<const bf16x8*>(kr1 + (st + HS) * 16);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int st = 0; st < HS; ++st) {
+        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][st], qf[st + HS], sacc[0], 0, 0, 0);
+        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][st], qf[st + HS], sacc[1], 0, 0, 0);
       }
     }
     // ---- causal mask + running softmax; element r of tile u is key kv0 + 32u + 8(r/4) + 4hl + r%4 ----
