@@ -61,8 +61,8 @@ def _check_decode_capture(stack, li, cap, sample, dtype):
         assert gu.rel_err(k_before[blk, :, slot].astype(np.float64), okc[blk, :, slot].astype(np.float64)) < TOL
 
 
-@pytest.mark.parametrize("n_kv", [0, 2])     # multi-head, and two query heads per key/value head
-def test_small_stack_runs_a_workload_to_completion_with_layerwise_parity(gpu, n_kv):
+@pytest.mark.parametrize("n_kv,overlap", [(0, False), (2, False), (0, True)])   # multi-head; two query heads per
+def test_small_stack_runs_a_workload_to_completion_with_layerwise_parity(gpu, n_kv, overlap):   # K/V head; overlapped hand-off
     shape = synth.ModelShape(hidden=512, n_heads=4, head_dim=128, ffn=2048, n_layers=4, n_kv_heads=n_kv)
     L, vocab = 4, 1024
     rng = np.random.default_rng(11)
@@ -70,7 +70,7 @@ def test_small_stack_runs_a_workload_to_completion_with_layerwise_parity(gpu, n_
     life = [synth.blocks_needed(r.prompt_len + r.output_len - 1, 16) for r in reqs]
     pool_blocks = max(life) * 3                                   # tight: admission has to wait for pages
     stack = inst.GpuStack(shape, L, 5, pool_blocks, max_batch=6, max_prefill_tokens=256, max_ctx=max(life) * 16,
-                          max_blocks_per_seq=max(life), vocab=vocab, n_pos=64)
+                          max_blocks_per_seq=max(life), vocab=vocab, n_pos=64, overlap_handoff=overlap)
     sched = inst.Scheduler(reqs, inst.BlockPool(pool_blocks, 5), 6, 256, 16, max(life))
     stack.capture = {0: [], 2: [], 3: []}
     raw = inst.run_workload(stack, sched)
@@ -90,13 +90,14 @@ def test_small_stack_runs_a_workload_to_completion_with_layerwise_parity(gpu, n_
             _check_decode_capture(stack, li, c, list(range(len(c["ctx"]))), np.float64)
 
 
-def test_small_stack_handoff_is_bit_exact_in_every_captured_layer(gpu):
+@pytest.mark.parametrize("overlap", [False, True])   # hand-off in line, or on a second stream beside the next layer
+def test_small_stack_handoff_is_bit_exact_in_every_captured_layer(gpu, overlap):
     shape = synth.ModelShape(hidden=512, n_heads=4, head_dim=128, ffn=2048, n_layers=3)
     lens = [33, 16, 1, 70]
     reqs = [inst.Request(i, l, 1) for i, l in enumerate(lens)]
     pool_blocks = 40
     stack = inst.GpuStack(shape, 3, 9, pool_blocks, max_batch=4, max_prefill_tokens=128, max_ctx=96,
-                          max_blocks_per_seq=6, vocab=512, n_pos=128)
+                          max_blocks_per_seq=6, vocab=512, n_pos=128, overlap_handoff=overlap)
     stack.k_pool.fill_(3.0)
     stack.v_pool.fill_(5.0)
     sched = inst.Scheduler(reqs, inst.BlockPool(pool_blocks, 2), 4, 128, 16, 6)
