@@ -21,6 +21,11 @@
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream); no call synchronises; outputs are valid once the
  *     caller has synchronised the stream.
+ *   - Calls record kernel launches only (no allocation, host copy or memset), so a
+ *     sequence of calls can be captured into a HIP graph; the first launch of a
+ *     kernel configuration sets a function attribute, so run the sequence once
+ *     eagerly before capturing it.  A context is not thread-safe: one thread at a
+ *     time per ds_ctx.
  *   - Errors are returned as ds_status; arguments are checked on the host
  *     before anything is launched.  Contents of device index arrays
  *     (cu_seqlens, block_tables, ctx_lens) are NOT validated: out-of-range
