@@ -137,7 +137,8 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
     }
     fetch(min(kv0 + kAttKV, (n_tiles - 1) * kAttKV));  // next tile (the last iteration re-fetches its own)
     __syncthreads();
-    if (kv0 > qw0 + 31) continue;  // every key of this tile is in the future of this wave's queries
+    // every key of this tile is in the future of this wave's queries, or the wave has no query at all
+    if (kv0 > qw0 + 31 || qw0 >= len) continue;
 
     // ---- S^T = K Q^T : two 32-key row tiles ----
     // The two row tiles advance together, so that consecutive matrix instructions write different
