@@ -186,6 +186,7 @@ def test_decode_attention(gpu, head_dim, n_heads, kv_lens):
     (10, 2, [2047, 5, 129]),                  # 5 per group (not a power of two): padded head columns stay out
     (16, 1, [300, 40]),                       # 16 per group = a full tile of heads
     (6, 1, [777]),                            # splits with an odd number of pages per split
+    (32, 1, [100, 33, 530]),                  # 32 per group: wider than a tile of heads, the per-head kernel serves it
 ])
 def test_decode_attention_grouped_query(gpu, n_heads, n_kv, kv_lens):
     """Query head j reads key/value head j / (n / n_kv) (grouped-query attention, Sec. 3.2); head size 128 takes
