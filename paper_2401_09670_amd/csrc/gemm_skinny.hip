@@ -281,23 +281,24 @@ __global__ __launch_bounds__(kSkThreads) void skinny_gemm_kernel(const SkinnyPar
 // streaming kernel needs is not many bytes in flight per CU but several streams per CU that do not
 // stall together - two independent 16 KB streams per CU reach 5.7 TB/s, one 64 KB stream 5.3.
 //
-// So: a workgroup (4 waves) owns 64 output columns over the whole K; its waves split K between them
+// So: a workgroup (4 waves; 3 for batches above 64 rows) owns 64 or 80 output columns over the whole K; its waves split K between them
 // 64-wide slab by slab (wave w takes slabs w, w+4, ...) and each wave runs its OWN two- or three-stage
 // direct-to-LDS ring [16, 32 or 64 activation rows | 64 or 80 weight rows] x 128 bytes, waiting on nothing but its
 // own loads - no barrier in the loop, four desynchronised streams per CU.  The four waves' 64 x 64
 // fp32 tiles are added through LDS at the end (fixed order) and wave w finishes column tile w.
 // grid = N / 64 workgroups, no partial sums in global memory, no second launch.
 // ---------------------------------------------------------------------------------------------
-constexpr int kWrThreads = 256;
 constexpr int kWrKS = 64;  // k elements per slab
 
 // NT = weight row tiles of 16 per workgroup (4 or 5: 64 or 80 output columns, whichever tiles N into
 // fewer rounds of 256 workgroups); MT = activation row tiles of 16 (1, 2 or 4: batches of up to 16, 32 or
 // 64 sequences - a small batch does not pay for 64 activation rows per slab: worth 2 us of a 158 us step at
 // OPT-13B, the rest of such a step is weight bytes and per-launch ramps); S = stages of a wave's ring (the
-// smaller stages of small batches leave room for a third: two slabs in flight per wave).
-template <int NT, int MT, int S>
-__global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyParams p) {
+// smaller stages of small batches leave room for a third: two slabs in flight per wave); NW = waves per
+// workgroup (4; 3 for batches of 65..128 sequences, whose stages of 128 activation rows fit the LDS three times
+// two, not four times two).
+template <int NT, int MT, int S, int NW>
+__global__ __launch_bounds__(64 * NW) void wring_gemm_kernel(const SkinnyParams p) {
   constexpr int kWrBN = 16 * NT, kWrBM = 16 * MT;
   constexpr int kWrStageElems = (kWrBM + kWrBN) * kWrKS;  // [BM X rows | BN W rows] x 64 k
   constexpr int kWrLoads = (kWrBM + kWrBN) / 8;           // wave-level loads (8 rows x 128 B) per slab
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyPara
   const int n0 = blockIdx.x * kWrBN;
   const int K = p.K;
   const int slabs_total = K / kWrKS;
-  const int ns = (slabs_total - wave + 3) / 4;  // this wave's slabs: wave, wave + 4, ...  (>= 1: K >= 256)
+  const int ns = (slabs_total - wave + NW - 1) / NW;  // this wave's slabs: wave, wave + NW, ...  (>= 1: K >= 256)
 
   // load j of a slab covers stage rows 8j .. 8j+7 (rows 0..BM-1 = X, then W); lane: row 8j + lane/8,
   // 16-byte chunk (lane%8) ^ ((row >> 1) & 7) - the swizzle that makes the fragment reads conflict-free
@@ -322,7 +323,7 @@ __global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyPara
   }
   uint16_t* ring = lds + wave * S * kWrStageElems;
   auto request = [&](int i, int st) {  // this wave's slab i (clamped: a harmless re-load) into its stage st
-    const int ofs = min(i, ns - 1) * 4 * kWrKS;
+    const int ofs = min(i, ns - 1) * NW * kWrKS;
     uint16_t* dst = ring + st * kWrStageElems;
 #pragma unroll
     for (int j = 0; j < kWrLoads; ++j)
@@ -378,7 +379,7 @@ __global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyPara
   // wave w finishes weight row tiles a = w (and w + 4): the four waves' tiles are added in wave order.
   // Lane: row m = 16t + lane%16, columns n = n0 + 16a + 4*(lane/16) + 0..3.
   const floatx4* red = reinterpret_cast<const floatx4*>(lds);
-  for (int a = wave; a < NT; a += 4) {
+  for (int a = wave; a < NT; a += NW) {
     const int n = n0 + 16 * a + (lane >> 4) * 4;
     if (n >= p.N) continue;
 #pragma unroll
@@ -387,7 +388,7 @@ __global__ __launch_bounds__(kWrThreads) void wring_gemm_kernel(const SkinnyPara
       if (m >= p.M) continue;
       floatx4 v = red[((0 * NT + a) * MT + t) * 64 + lane];
 #pragma unroll
-      for (int w2 = 1; w2 < 4; ++w2) v += red[((w2 * NT + a) * MT + t) * 64 + lane];
+      for (int w2 = 1; w2 < NW; ++w2) v += red[((w2 * NT + a) * MT + t) * 64 + lane];
       float v0 = v[0], v1 = v[1], v2 = v[2], v3 = v[3];
       if (p.bias) {
         const u32x2 bb = *reinterpret_cast<const u32x2*>(p.bias + n);
@@ -700,11 +701,11 @@ static hipError_t launch_skinny_cfg(const SkinnyParams& p, int splits, hipStream
   return hipGetLastError();
 }
 
-template <int NT, int MT, int S>
+template <int NT, int MT, int S, int NW>
 static hipError_t launch_wring_cfg(const SkinnyParams& p, hipStream_t stream) {
-  constexpr size_t lds_bytes = (size_t)4 * S * (16 * MT + 16 * NT) * kWrKS * sizeof(uint16_t);  // 4 waves x S stages
-  static_assert(lds_bytes <= 160 * 1024 && (size_t)4 * NT * MT * 1024 <= lds_bytes, "LDS");
-  auto kern = wring_gemm_kernel<NT, MT, S>;
+  constexpr size_t lds_bytes = (size_t)NW * S * (16 * MT + 16 * NT) * kWrKS * sizeof(uint16_t);  // NW waves x S stages
+  static_assert(lds_bytes <= 160 * 1024 && (size_t)NW * NT * MT * 1024 <= lds_bytes, "LDS");
+  auto kern = wring_gemm_kernel<NT, MT, S, NW>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -712,7 +713,7 @@ static hipError_t launch_wring_cfg(const SkinnyParams& p, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3((p.N + 16 * NT - 1) / (16 * NT)), dim3(kWrThreads), lds_bytes, stream, p);
+  hipLaunchKernelGGL(kern, dim3((p.N + 16 * NT - 1) / (16 * NT)), dim3(64 * NW), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
@@ -720,25 +721,30 @@ static hipError_t launch_wring_cfg(const SkinnyParams& p, hipStream_t stream) {
 static hipError_t launch_wring(int nt, const SkinnyParams& p, hipStream_t stream) {
   const int M = p.M;
   if (nt == 5) {
-    if (M <= 16) return launch_wring_cfg<5, 1, 3>(p, stream);  // 144 KB
-    if (M <= 32) return launch_wring_cfg<5, 2, 2>(p, stream);  // 112 KB
-    return launch_wring_cfg<5, 4, 2>(p, stream);               // 144 KB
+    if (M <= 16) return launch_wring_cfg<5, 1, 3, 4>(p, stream);  // 144 KB
+    if (M <= 32) return launch_wring_cfg<5, 2, 2, 4>(p, stream);  // 112 KB
+    if (M <= 64) return launch_wring_cfg<5, 4, 2, 4>(p, stream);  // 144 KB
+    return launch_wring_cfg<5, 8, 2, 3>(p, stream);               // 156 KB
   }
-  if (M <= 16) return launch_wring_cfg<4, 1, 3>(p, stream);    // 120 KB
-  if (M <= 32) return launch_wring_cfg<4, 2, 3>(p, stream);    // 144 KB
-  return launch_wring_cfg<4, 4, 2>(p, stream);                 // 128 KB
+  if (M <= 16) return launch_wring_cfg<4, 1, 3, 4>(p, stream);    // 120 KB
+  if (M <= 32) return launch_wring_cfg<4, 2, 3, 4>(p, stream);    // 144 KB
+  if (M <= 64) return launch_wring_cfg<4, 4, 2, 4>(p, stream);    // 128 KB
+  return launch_wring_cfg<4, 8, 2, 3>(p, stream);                 // 144 KB
 }
 
 // Column-tile width (in 16-row tiles) for the wave-private-ring kernel, or 0 if the shape is not one it
-// is good at: up to 64 rows, K a multiple of 256, and enough column tiles to occupy most of the chip
-// without splitting K.
+// is good at: K a multiple of 256 and enough column tiles to occupy most of the chip without splitting K.
+// Up to 64 rows it takes both widths; for 65..128 rows only the 80-column one, where a workgroup re-reads 1.6
+// activation bytes per weight byte rather than 2 (measured at 128 rows: FFN-in of OPT-13B / 66B and QKV of
+// OPT-175B 18-27 % faster than the split-K ring kernel, every 64-column shape equal or up to 20 % slower).
 int g_skinny_wring = 1;  // development switch: 0 = never use the wave-private-ring kernel
 static int wring_tiles(int M, int N, int K) {
-  if (!g_skinny_wring || M > 64 || K < 256 || K % 256 != 0) return 0;
+  if (!g_skinny_wring || M > 128 || K < 256 || K % 256 != 0) return 0;
   const int t4 = (N + 63) / 64, t5 = (N + 79) / 80;
   const int r4 = (t4 + 255) / 256, r5 = (t5 + 255) / 256;
   const int nt = r5 < r4 ? 5 : 4;
   const int tiles = nt == 5 ? t5 : t4;
+  if (M > 64 && nt != 5) return 0;
   return tiles >= 160 ? nt : 0;
 }
 

@@ -114,6 +114,8 @@ def test_linear_tile_path(gpu, rows, in_f, out_f, bias, relu, residual):
     # and column-tile width (64 columns at 10240, 80 at 20480)
     (1, 512, 10240, True, False, False), (16, 256, 20480, True, True, False), (17, 768, 10240, False, False, True),
     (32, 512, 20480, True, False, True), (33, 256, 10240, True, True, False), (9, 1024, 20480, False, False, False),
+    (65, 256, 20480, True, True, False), (100, 768, 20480, False, False, True), (128, 512, 20480, True, False, True),
+    (128, 512, 10240, True, False, False),    # 64-column shape above 64 rows: stays on the split-K ring kernel
 ])
 def test_linear_skinny_path(gpu, rows, in_f, out_f, bias, relu, residual):
     ctx = gu.make_ctx(synth.TINY)
