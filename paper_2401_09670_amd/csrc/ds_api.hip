@@ -129,16 +129,16 @@ size_t linear_ws_exact(int rows, int in_f, int out_f) {
 }
 
 // ... and for any row count up to `rows` (fewer rows can mean more splits), so that a workspace sized
-// for a maximum serves every smaller call.  The plans only change with the row count rounded up to 64.
+// for a maximum serves every smaller call.  Up to 256 rows the plan may change with every row count; above,
+// only with the number of row tiles (multiples of 64).
 size_t linear_ws(int rows, int in_f, int out_f) {
   size_t need = 0;
-  for (int r = 64;; r += 64) {
-    const int rr = r < rows ? r : rows;
-    const size_t b = linear_ws_exact(rr, in_f, out_f);
+  for (int r = 1; r <= rows; r = r < 256 ? r + 1 : r + 64) {
+    const size_t b = linear_ws_exact(r, in_f, out_f);
     if (b > need) need = b;
-    if (rr == rows) break;
   }
-  return need;
+  const size_t b = linear_ws_exact(rows, in_f, out_f);
+  return b > need ? b : need;
 }
 
 size_t max_gemm_ws(const ds_model_cfg& c, int rows) {

@@ -442,6 +442,36 @@ struct GemmPlan {
 // Tile shape by the cost model above; split count so that a launch with few tiles still occupies the
 // chip.  Measured on the decode shapes (M <= 256): >= ~100 workgroups of 128 weight rows stream at
 // 5-6 TB/s unsplit; 40 tiles need 4-6 splits; more than ~250 workgroups gain nothing.
+// Up to 256 rows the product is bound by streaming the weights, not by the matrix cores, and what a launch
+// costs is the bytes its busiest compute unit has to pull through its load path (about 35 GB/s per unit,
+// activation re-reads out of L2 included): rounds x (weight + activation bytes of a workgroup's K share
+// + its partial tile), plus the reduce pass when K is split.  Used where the rule below would start a second,
+// mostly empty round (FFN-in of OPT-13B at 256 rows: 320 tiles of 128x128, 111 us; re-planned 77 us).  For
+// single-round launches the measured split counts of the rule below beat this model by 5-25 %, so it is
+// not applied to them.
+static GemmPlan decode_plan(int M, int N, int K) {
+  static const int kBm[5] = {0, 256, 128, 256, 64}, kBn[5] = {0, 160, 128, 256, 128};
+  const int kt = K / kBK;
+  const int max_s = kt / 8 > 0 ? (kt / 8 < 32 ? kt / 8 : 32) : 1;  // at least 8 k-tiles per split
+  GemmPlan best{2, 1};
+  double best_cost = 1e30;
+  for (int v = 1; v <= 4; ++v) {
+    const long tm = (M + kBm[v] - 1) / kBm[v], tn = (N + kBn[v] - 1) / kBn[v];
+    const double rows = (double)M / tm;  // activation rows a tile really has
+    for (int sp = 1; sp <= max_s; ++sp) {
+      const long wgs = tm * tn * sp;
+      const double rounds = (double)((wgs + 255) / 256);
+      double cost = rounds * ((kBn[v] + rows) * ((double)K / sp) * 2.0 + (sp > 1 ? kBm[v] * kBn[v] * 4.0 : 0.0));
+      if (sp > 1) cost += (double)sp * M * N * 4.0 / 256.0 + 175e3;  // reduce pass: its reads, and about 5 us
+      if (cost < best_cost) {
+        best_cost = cost;
+        best = GemmPlan{v, sp};
+      }
+    }
+  }
+  return best;
+}
+
 static GemmPlan gemm_plan(int M, int N, int K) {
   GemmPlan pl{1, 1};
   if (M <= 64) {
@@ -466,6 +496,8 @@ static GemmPlan gemm_plan(int M, int N, int K) {
     pl.splits = s;
   }
   if (g_gemm_splits > 0) pl.splits = g_gemm_splits < kt ? g_gemm_splits : kt;
+  // decode-sized launch that would need a second, mostly empty round: re-plan by bytes per compute unit
+  if (M <= 256 && tiles * pl.splits > 256 && g_gemm_variant == 0 && g_gemm_splits == 0) return decode_plan(M, N, K);
   return pl;
 }
 
