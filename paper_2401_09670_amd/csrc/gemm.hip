@@ -33,6 +33,7 @@ struct GemmParams {
   int ldx;     // row stride of X in elements (>= K)
   int ld_out;  // row stride of out[0]
   int ld_res;  // row stride of residual
+  int n_base;  // first output column of this launch (a launch may cover the columns [n_base, N) only)
   // Split-K (gridDim.y = S > 1): split s multiplies k-tiles s, s + S, ... and stores its fp32
   // accumulators to partial[s][M][N]; the epilogue then belongs to whoever adds the partials.
   float* partial;
@@ -118,7 +119,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   int tile_m, tile_n;
   patch_tile(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
   const int m0 = tile_m * BM;
-  const int n0 = tile_n * BN;
+  const int n0 = p.n_base + tile_n * BN;
   const int K = p.K;
   // Split-K deals the k-tiles round-robin (split s takes tiles s, s + S, ...), as the weight-streaming
   // kernel does: the splits of one output tile read neighbouring 128-byte pieces of the same rows at
@@ -396,7 +397,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int EPI>
 static hipError_t launch_dl_epi(GemmParams p, int splits, hipStream_t stream) {
   p.tiles_m = (p.M + BM - 1) / BM;
-  p.tiles_n = (p.N + BN - 1) / BN;
+  p.tiles_n = (p.N - p.n_base + BN - 1) / BN;
   constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * kBK * sizeof(uint16_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS");
   auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, EPI>;
@@ -562,6 +563,7 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
   p.ldx = ep.x_ld > 0 ? ep.x_ld : K;
   p.ld_out = ep.out_ld > 0 ? ep.out_ld : ep.seg_cols;
   p.ld_res = N;
+  p.n_base = 0;
   p.M = M; p.N = N; p.K = K;
   p.relu = ep.relu;
   p.tiles_m = p.tiles_n = 0;
@@ -584,19 +586,14 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
     if (fused_done) *fused_done = true;
   }
   hipError_t e;
-  const int n1 = (pl.splits == 1 && !p.k_cache && ep.seg_cols == N) ? tail_split_columns(M, N, pl.variant) : 0;
+  const int n1 = (pl.splits == 1 && !p.k_cache) ? tail_split_columns(M, N, pl.variant) : 0;
   if (n1 > 0) {
     // Leading columns on the large tile in (nearly) whole rounds of 256 workgroups, the rest on 128x128 tiles:
-    // two launches over disjoint column ranges of the same product.
+    // two launches over disjoint column ranges [0, n1) and [n1, N) of the same product (same operands, bias,
+    // residual and output segments; only the column range differs).
     GemmParams a = p, b = p;
     a.N = n1;
-    a.seg_cols = a.seg_cols_kv = n1;
-    b.W = p.W + (size_t)n1 * K;
-    b.bias = p.bias ? p.bias + n1 : nullptr;
-    b.residual = p.residual ? p.residual + n1 : nullptr;
-    b.out[0] = p.out[0] + n1;
-    b.N = N - n1;
-    b.seg_cols = b.seg_cols_kv = N - n1;
+    b.n_base = n1;
     e = pl.variant == 3 ? launch_dl<256, 256, 2, 2, 2, false>(a, 1, stream)
                         : launch_dl<256, 160, 4, 1, 3, false>(a, 1, stream);
     if (e != hipSuccess) return e;
