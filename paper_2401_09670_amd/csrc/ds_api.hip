@@ -6,7 +6,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "../../include/ds.h"
@@ -22,6 +24,10 @@ struct ds_ctx {
   };
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
+  // Workspace sizes already worked out (they walk every smaller row count through the GEMM planners, tens of
+  // microseconds; every ds_prefill / ds_decode_step call checks its workspace against them).
+  mutable std::map<int, size_t> prefill_ws;
+  mutable std::map<std::pair<int, int>, size_t> decode_ws;
 };
 
 namespace {
@@ -201,15 +207,23 @@ const char* ds_last_error(const ds_ctx* ctx) { return ctx ? ctx->err : "ctx is N
 
 size_t ds_prefill_workspace_bytes(const ds_ctx* ctx, int32_t max_tokens) {
   if (!ctx || max_tokens <= 0) return 0;
+  const auto hit = ctx->prefill_ws.find(max_tokens);
+  if (hit != ctx->prefill_ws.end()) return hit->second;
   const ds_model_cfg& c = ctx->cfg;
   const size_t th = align_up((size_t)max_tokens * c.hidden * 2, 256);
   const size_t tm = align_up((size_t)max_tokens * (c.ffn + kRowPad) * 2, 256);
   // a (LN out, reused for LN2), q, o, x1, u (rows padded), + split-K partials of the GEMMs
-  return 4 * th + tm + align_up(max_gemm_ws(c, max_tokens), 256);
+  const size_t need = 4 * th + tm + align_up(max_gemm_ws(c, max_tokens), 256);
+  if (ctx->prefill_ws.size() < 4096) ctx->prefill_ws[max_tokens] = need;
+  return need;
 }
 
 size_t ds_decode_workspace_bytes(const ds_ctx* ctx, int32_t max_batch, int32_t max_ctx) {
   if (!ctx || max_batch <= 0 || max_ctx <= 0) return 0;
+  // the attention partials depend on max_ctx only through its page count
+  const std::pair<int, int> key(max_batch, (max_ctx + 15) / 16);
+  const auto hit = ctx->decode_ws.find(key);
+  if (hit != ctx->decode_ws.end()) return hit->second;
   const ds_model_cfg& c = ctx->cfg;
   const size_t bh = align_up((size_t)max_batch * c.hidden * 2, 256);
   const size_t b3h = align_up((size_t)max_batch * qkv_width(c) * 2, 256);
@@ -223,7 +237,9 @@ size_t ds_decode_workspace_bytes(const ds_ctx* ctx, int32_t max_batch, int32_t m
   att = align_up(att, 256);
   const size_t sk = align_up(max_gemm_ws(c, max_batch), 256);
   // a, qkv, o, x1, u, attention partials, split-K partials
-  return 3 * bh + b3h + bm + att + sk;
+  const size_t need = 3 * bh + b3h + bm + att + sk;
+  if (ctx->decode_ws.size() < 4096) ctx->decode_ws[key] = need;
+  return need;
 }
 
 ds_status ds_layernorm(ds_ctx* ctx, const void* x, const void* gamma, const void* beta, int32_t rows,
