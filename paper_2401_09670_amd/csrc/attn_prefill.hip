@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
   }
 }
 
-int g_attn_force_order = -1;  // development switch: 0/1 force the workgroup order, -1 choose by grid size
+DS_SWITCH(g_attn_force_order, -1);  // 0/1 force the workgroup order, -1 choose by grid size
 
 hipError_t launch_prefill_attention(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
                                     int B, int max_seqlen, int n_heads, int n_kv_heads, int head_dim, void* o,

@@ -4,6 +4,15 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Development switches (force a tile shape, a split count, a kernel choice): plain constants in the library
+// build, so the choice logic they sit in folds away; the timing harnesses compile the sources with
+// -DDS_DEV_SWITCHES and flip them at run time.
+#ifdef DS_DEV_SWITCHES
+#define DS_SWITCH(name, value) int name = value
+#else
+#define DS_SWITCH(name, value) static constexpr int name = value
+#endif
+
 namespace ds {
 
 typedef __bf16 bf16_t;

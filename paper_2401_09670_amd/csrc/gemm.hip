@@ -432,8 +432,8 @@ static double tile_cost(int M, int N, int BM, int BN, double factor) {
   return rounds * BM * BN * factor;
 }
 
-int g_gemm_variant = 0;  // development switches (timing harness only): 0 = cost model, 1..4 force a tile
-int g_gemm_splits = 0;   // 0 = plan, > 0 force the split count
+DS_SWITCH(g_gemm_variant, 0);  // 0 = cost model, 1..4 force a tile
+DS_SWITCH(g_gemm_splits, 0);   // 0 = plan, > 0 force the split count
 
 struct GemmPlan {
   int variant;  // 1: 256x160, 2: 128x128, 3: 256x256, 4: 64x128
@@ -506,7 +506,7 @@ static GemmPlan gemm_plan(int M, int N, int K) {
 // product is cut at a column: the leading n1 columns keep the large tile and fill their rounds (nearly)
 // completely, the remaining ones take 128x128 tiles, whose last round wastes a quarter as much.  Returns n1, or
 // 0 to leave the launch whole.  Costs in the units of tile_cost.
-int g_gemm_tail_split = 1;  // development switch (timing harness only)
+DS_SWITCH(g_gemm_tail_split, 1);  // 0 = never cut a product at a column
 static int tail_split_columns(int M, int N, int variant) {
   if (!g_gemm_tail_split || (variant != 1 && variant != 3)) return 0;
   const int bm = 256, bn = variant == 1 ? 160 : 256;

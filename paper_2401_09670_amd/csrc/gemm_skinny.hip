@@ -629,8 +629,8 @@ __global__ __launch_bounds__(256) void skinny_reduce_kv_kernel(const SkinnyParam
   st16(dst, ov);
 }
 
-int g_skinny_force_ntw = 0;  // development switches (timing harness only): 0 = byte model
-int g_skinny_force_splits = 0;
+DS_SWITCH(g_skinny_force_ntw, 0);  // 0 = byte model
+DS_SWITCH(g_skinny_force_splits, 0);
 
 struct SkinnyPlan {
   int ntw;     // column tiles per wave: BN = 64 * ntw
@@ -737,7 +737,7 @@ static hipError_t launch_wring(int nt, const SkinnyParams& p, hipStream_t stream
 // Up to 64 rows it takes both widths; for 65..128 rows only the 80-column one, where a workgroup re-reads 1.6
 // activation bytes per weight byte rather than 2 (measured at 128 rows: FFN-in of OPT-13B / 66B and QKV of
 // OPT-175B 18-27 % faster than the split-K ring kernel, every 64-column shape equal or up to 20 % slower).
-int g_skinny_wring = 1;  // development switch: 0 = never use the wave-private-ring kernel
+DS_SWITCH(g_skinny_wring, 1);  // 0 = never use the wave-private-ring kernel
 static int wring_tiles(int M, int N, int K) {
   if (!g_skinny_wring || M > 128 || K < 256 || K % 256 != 0) return 0;
   const int t4 = (N + 63) / 64, t5 = (N + 79) / 80;
