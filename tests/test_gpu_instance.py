@@ -168,3 +168,27 @@ def test_opt13b_40_layer_stack_first_middle_last_layer_parity(gpu):
     for i in (shortest, longest):
         for j in (0, lens[i] // 2, lens[i] - 1):
             assert np.array_equal(kg[table[i, j // 16], :, j % 16], ksrc[cu[i] + j])
+
+
+def test_small_stack_decodes_preloaded_contexts(gpu):
+    """Decode-only workloads (the OPT-175B stage's decode batch): contexts that no prefill here produced sit in
+    pool pages as seeded random K/V; the loop decodes over them with page growth, every step checked per layer."""
+    shape = synth.ModelShape(hidden=512, n_heads=4, head_dim=128, ffn=2048, n_layers=3)
+    ctxs = [40, 17, 100, 1, 64, 16]
+    reqs = [inst.Request(i, c, 4, preloaded=True) for i, c in enumerate(ctxs)]     # 3 decoding steps each
+    life = [synth.blocks_needed(c + 3, 16) for c in ctxs]
+    pool_blocks = sum(life) + 2
+    stack = inst.GpuStack(shape, 3, 21, pool_blocks, max_batch=len(reqs), max_prefill_tokens=16,
+                          max_ctx=max(life) * 16, max_blocks_per_seq=max(life), vocab=512, n_pos=128)
+    stack.k_pool.fill_(float("nan"))          # what is not filled below must never matter
+    stack.v_pool.fill_(float("-inf"))
+    sched = inst.Scheduler(reqs, inst.BlockPool(pool_blocks, 3), len(reqs), 16, 16, max(life))
+    stack.capture = {0: [], 2: []}
+    raw = inst.run_workload(stack, sched)
+    assert raw["finished"] == len(reqs) and not raw["prefills"] and len(raw["steps"]) == 3
+    assert [s["batch"] for s in raw["steps"]] == [len(reqs)] * 3
+    for li, caps in stack.capture.items():
+        assert len(caps) == 3
+        for c in caps:
+            assert np.all(np.isfinite(gu.to_f64(c["y"])))
+            _check_decode_capture(stack, li, c, list(range(len(ctxs))), np.float64)
