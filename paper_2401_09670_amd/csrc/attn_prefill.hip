@@ -18,7 +18,6 @@ constexpr int kAttThreads = 256;
 constexpr int kAttQ = 128;    // queries per workgroup
 constexpr int kAttKV = 64;    // keys per tile
 constexpr float kSlack = 8.f;   // exponent headroom before the softmax reference point is moved
-constexpr int kVtStride = kAttKV + 4;  // elements per V^T row (136 B): 8-byte reads of 16 rows hit distinct banks
 
 template <int HD>
 __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))) void prefill_attention_kernel(
@@ -30,7 +29,9 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
   constexpr int DSTEPS = HD / 16;   // MFMA k-steps over the head dimension
   constexpr int DT = HD / 32;       // 32-row tiles of O^T
   __shared__ __attribute__((aligned(16))) uint16_t ks[kAttKV * KS];
-  __shared__ __attribute__((aligned(16))) uint16_t vt[HD * kVtStride];
+  constexpr int VS = HD + 32;       // V tile row stride in elements (64 bytes of padding: the four rows a
+                                    // 16-lane group reads transposed start 16 banks apart)
+  __shared__ __attribute__((aligned(16))) uint16_t vs[kAttKV * VS];
 
   // Workgroups reach the chip's eight partitions (each with its own L2) round-robin in launch
   // order, so id % 8 names the partition and id / 8 the order inside it.  A (request, head) pair is
@@ -83,30 +84,22 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
   // is covered by the matrix work of tile i.
   constexpr int CPR = HD / 8;                                  // 16-byte chunks per K/V row
   constexpr int KITER = kAttKV * CPR / kAttThreads;            // K chunks per thread per tile
-  constexpr int VITER = (kAttKV / 2) * CPR / kAttThreads;      // V items (2 keys x 8 dims) per thread per tile
-  u32x4 kreg[KITER], vreg0[VITER], vreg1[VITER];
-  const int krow = tid / CPR, kch = tid % CPR;                 // K: this thread's row (+ 16 i) and chunk
-  const int vpair = tid % (kAttKV / 2), vch = tid / (kAttKV / 2);  // V: key pair and chunk (+ 8 i)
+  u32x4 kreg[KITER], vreg[KITER];
+  const int krow = tid / CPR, kch = tid % CPR;                 // this thread's K and V row (+ 16 i) and chunk
   auto fetch = [&](int kv0) {
     if (kv0 + kAttKV <= len) {  // whole tile inside the request: plain strided addresses
       const uint16_t* kp = kbase + (size_t)(kv0 + krow) * hk + kch * 8;
+      const uint16_t* vp = vbase + (size_t)(kv0 + krow) * hk + kch * 8;
 #pragma unroll
       for (int i = 0; i < KITER; ++i) kreg[i] = ld16(kp + (size_t)i * (kAttThreads / CPR) * hk);
-      const uint16_t* vp = vbase + (size_t)(kv0 + 2 * vpair) * hk + vch * 8;
 #pragma unroll
-      for (int i = 0; i < VITER; ++i) {
-        vreg0[i] = ld16(vp + i * (kAttThreads / (kAttKV / 2)) * 8);
-        vreg1[i] = ld16(vp + hk + i * (kAttThreads / (kAttKV / 2)) * 8);
-      }
+      for (int i = 0; i < KITER; ++i) vreg[i] = ld16(vp + (size_t)i * (kAttThreads / CPR) * hk);
     } else {  // ragged tail: rows past the end repeat the last key (they are masked out below)
 #pragma unroll
-      for (int i = 0; i < KITER; ++i)
-        kreg[i] = ld16(kbase + (size_t)min(kv0 + krow + i * (kAttThreads / CPR), len - 1) * hk + kch * 8);
-#pragma unroll
-      for (int i = 0; i < VITER; ++i) {
-        const int ch = vch + i * (kAttThreads / (kAttKV / 2));
-        vreg0[i] = ld16(vbase + (size_t)min(kv0 + 2 * vpair, len - 1) * hk + ch * 8);
-        vreg1[i] = ld16(vbase + (size_t)min(kv0 + 2 * vpair + 1, len - 1) * hk + ch * 8);
+      for (int i = 0; i < KITER; ++i) {
+        const size_t row = (size_t)min(kv0 + krow + i * (kAttThreads / CPR), len - 1);
+        kreg[i] = ld16(kbase + row * hk + kch * 8);
+        vreg[i] = ld16(vbase + row * hk + kch * 8);
       }
     }
   };
@@ -122,18 +115,12 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
       const int r = c / CPR, ch = c % CPR;
       st16(ks + r * KS + ch * 8, kreg[i]);
     }
-    // ---- stage V tile transposed: vt[d][key]; a thread holds two adjacent keys x 8 dims ----
+    // ---- stage V tile [64][HD] row-major as well; the transposition happens in the fragment reads ----
 #pragma unroll
-    for (int i = 0; i < VITER; ++i) {
+    for (int i = 0; i < KITER; ++i) {
       const int c = tid + i * kAttThreads;
-      const int pair = c % (kAttKV / 2), ch = c / (kAttKV / 2);
-      const u32x4 a = vreg0[i], b = vreg1[i];
-      uint32_t* dst = reinterpret_cast<uint32_t*>(vt + (ch * 8) * kVtStride + 2 * pair);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        dst[(2 * j) * (kVtStride / 2)] = (a[j] & 0xffffu) | (b[j] << 16);
-        dst[(2 * j + 1) * (kVtStride / 2)] = (a[j] >> 16) | (b[j] & 0xffff0000u);
-      }
+      const int r = c / CPR, ch = c % CPR;
+      st16(vs + r * VS + ch * 8, vreg[i]);
     }
     fetch(min(kv0 + kAttKV, (n_tiles - 1) * kAttKV));  // next tile (the last iteration re-fetches its own)
     __syncthreads();
@@ -219,20 +206,26 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
     l_run += psum;
 
     // ---- O^T += V^T P^T.  PV step (u,v) contracts keys 32u+16v + {0..3, 8..11} + 4hl ----
+    // The V^T fragments come out of the row-major tile through the transposing LDS read: in a group of 16
+    // lanes, lane j hands in the address of 4 consecutive d of key j / 4 (16 d in all, 4 keys), and lane i
+    // gets back the 4 keys at d = i.  Groups 0, 1 serve d 0..15, 16..31 of key group hl = 0, groups 2, 3 of hl = 1.
+    const int i16 = lane & 15;
+    const uint16_t* vfrag = vs + (4 * hl + (i16 >> 2)) * VS + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int vv = 0; vv < 2; ++vv) {
-        const int kb = u * 32 + vv * 16 + hl * 4;
+        const uint16_t* vstep = vfrag + (u * 32 + vv * 16) * VS;
 #pragma unroll
         for (int d = 0; d < DT; ++d) {
-          const uint16_t* vr = vt + (d * 32 + lq) * kVtStride + kb;
-          const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vr);
-          const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vr + 8);
-          bf16x8 vf;
-          vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
-          vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
-          oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[2 * u + vv], oacc[d], 0, 0, 0);
+          typedef short short4v __attribute__((ext_vector_type(4)));
+          typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vstep + d * 32));
+          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vstep + 8 * VS + d * 32));
+          u32x4 packed;
+          const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+          packed[0] = l2[0]; packed[1] = l2[1]; packed[2] = h2[0]; packed[3] = h2[1];
+          oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, packed), pf[2 * u + vv], oacc[d], 0, 0, 0);
         }
       }
   }
