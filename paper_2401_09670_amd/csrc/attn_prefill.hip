@@ -7,8 +7,9 @@
 // max / sum / rescale factors are per-lane scalars, and the probabilities are
 // already in the register layout the second product O^T[d, query] = V^T P^T
 // needs as its column operand - no shuffles, no LDS round trip for P.
-// K is staged in LDS row-major, V transposed ([d][key]) so a lane's V^T
-// fragment is two 8-byte reads.
+// K and V tiles arrive row-major by direct global->LDS loads into two buffers (tile i+1 lands while tile i
+// is multiplied); the V^T fragments of the second product come out of the row-major V tile through the
+// transposing LDS read.
 #include "common.h"
 #include "kernels.h"
 
@@ -25,13 +26,17 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
     const int32_t* __restrict__ cu_seqlens, uint16_t* __restrict__ o, int n_heads, int kv_group,
     float scale_log2e,
     int n_pairs, int pairs_per_xcd, int n_qt, int qt_fast) {
-  constexpr int KS = HD + 8;        // K tile row stride in elements
   constexpr int DSTEPS = HD / 16;   // MFMA k-steps over the head dimension
   constexpr int DT = HD / 32;       // 32-row tiles of O^T
-  __shared__ __attribute__((aligned(16))) uint16_t ks[kAttKV * KS];
-  constexpr int VS = HD + 32;       // V tile row stride in elements (64 bytes of padding: the four rows a
-                                    // 16-lane group reads transposed start 16 banks apart)
-  __shared__ __attribute__((aligned(16))) uint16_t vs[kAttKV * VS];
+  constexpr int CPR = HD / 8;       // 16-byte chunks per K/V row
+  // Two LDS buffers of [K tile | V tile], each tile 64 rows of HD elements, row-major and unpadded: the tiles
+  // arrive by direct global->LDS loads (a wave-level load drops 64 consecutive 16-byte pieces), so bank conflicts
+  // are avoided by storing chunk c of row r at position c ^ swizzle(r), applied on the global side of the load.
+  //   K (16-byte fragment reads of 32 consecutive rows at one chunk index): rows of 256 bytes r & 15, of 128 bytes (r >> 1) & 7.
+  //   V (transposing 8-byte reads: 4 consecutive rows x 4 consecutive chunks per half wave): (r & 3) << 2 for
+  //   256-byte rows; ((r >> 1) & 1) << 2 for 128-byte rows, whose neighbours already sit in different bank halves.
+  constexpr int TILE_ELEMS = kAttKV * HD, BUF_ELEMS = 2 * TILE_ELEMS;
+  extern __shared__ __attribute__((aligned(1024))) uint16_t att_lds[];
 
   // Workgroups reach the chip's eight partitions (each with its own L2) round-robin in launch
   // order, so id % 8 names the partition and id / 8 the order inside it.  A (request, head) pair is
@@ -80,52 +85,50 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
   const int kv_end = min(len, q0 + kAttQ);  // keys any query of this workgroup may see
   const int n_tiles = (kv_end + kAttKV - 1) / kAttKV;
 
-  // K/V tiles are fetched one tile ahead into registers, so the global-memory latency of tile i+1
-  // is covered by the matrix work of tile i.
-  constexpr int CPR = HD / 8;                                  // 16-byte chunks per K/V row
-  constexpr int KITER = kAttKV * CPR / kAttThreads;            // K chunks per thread per tile
-  u32x4 kreg[KITER], vreg[KITER];
-  const int krow = tid / CPR, kch = tid % CPR;                 // this thread's K and V row (+ 16 i) and chunk
-  auto fetch = [&](int kv0) {
-    if (kv0 + kAttKV <= len) {  // whole tile inside the request: plain strided addresses
-      const uint16_t* kp = kbase + (size_t)(kv0 + krow) * hk + kch * 8;
-      const uint16_t* vp = vbase + (size_t)(kv0 + krow) * hk + kch * 8;
+  // Tile i+1 is requested (global -> LDS, no registers) into the other buffer before tile i is multiplied; one
+  // workgroup barrier per tile: it closes the reads of tile i and publishes tile i+1.
+  constexpr int NLD = kAttKV * CPR / kAttThreads;   // wave-level loads per wave, tile and operand (4 or 2)
+  int ld_row[NLD], ld_kcol[NLD], ld_vcol[NLD];      // this lane's tile row and (swizzled) source column of load j
 #pragma unroll
-      for (int i = 0; i < KITER; ++i) kreg[i] = ld16(kp + (size_t)i * (kAttThreads / CPR) * hk);
+  for (int j = 0; j < NLD; ++j) {
+    const int piece = (wave * NLD + j) * 64 + lane;  // 16-byte piece of the tile this lane's data lands in
+    const int r = piece / CPR, c = piece % CPR;
+    ld_row[j] = r;
+    ld_kcol[j] = (c ^ (CPR == 16 ? (r & 15) : ((r >> 1) & 7))) * 8;
+    ld_vcol[j] = (c ^ (CPR == 16 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2))) * 8;
+  }
+  auto request = [&](int kv0, int buf) {  // rows past the end repeat the last key (they are masked out below)
+    uint16_t* kdst = att_lds + buf * BUF_ELEMS + (wave * NLD) * 512;
 #pragma unroll
-      for (int i = 0; i < KITER; ++i) vreg[i] = ld16(vp + (size_t)i * (kAttThreads / CPR) * hk);
-    } else {  // ragged tail: rows past the end repeat the last key (they are masked out below)
-#pragma unroll
-      for (int i = 0; i < KITER; ++i) {
-        const size_t row = (size_t)min(kv0 + krow + i * (kAttThreads / CPR), len - 1);
-        kreg[i] = ld16(kbase + row * hk + kch * 8);
-        vreg[i] = ld16(vbase + row * hk + kch * 8);
-      }
+    for (int j = 0; j < NLD; ++j) {
+      const size_t row = (size_t)min(kv0 + ld_row[j], len - 1) * hk;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + row + ld_kcol[j]),
+                                       (__attribute__((address_space(3))) void*)(kdst + j * 512), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + row + ld_vcol[j]),
+                                       (__attribute__((address_space(3))) void*)(kdst + TILE_ELEMS + j * 512), 16, 0, 0);
     }
   };
-  fetch(0);
+  auto wait_loads = [] {  // s_waitcnt vmcnt(0) only: vmcnt[3:0] | expcnt=7 | lgkmcnt=15 | vmcnt[5:4] in bits 15:14
+    __builtin_amdgcn_s_waitcnt((0x7 << 4) | (0xf << 8));
+  };
+  request(0, 0);
+  wait_loads();
+  __syncthreads();
 
+  const int kswz = CPR == 16 ? (lq & 15) : ((lq >> 1) & 7);   // K fragment rows are u*32 + lq
   for (int tile = 0; tile < n_tiles; ++tile) {
     const int kv0 = tile * kAttKV;
-    __syncthreads();  // previous tile's LDS reads are done
-    // ---- stage K tile [64][HD] row-major ----
-#pragma unroll
-    for (int i = 0; i < KITER; ++i) {
-      const int c = tid + i * kAttThreads;
-      const int r = c / CPR, ch = c % CPR;
-      st16(ks + r * KS + ch * 8, kreg[i]);
+    const uint16_t* ks = att_lds + (tile & 1) * BUF_ELEMS;
+    const uint16_t* vs = ks + TILE_ELEMS;
+    // the other buffer was last read in iteration tile-1, which every wave left through the barrier below
+    if (tile + 1 < n_tiles) request(kv0 + kAttKV, (tile + 1) & 1);
+    // nothing to multiply if every key of this tile is in the future of this wave's queries, or the wave has no
+    // query at all; the wave still takes part in the loads and the barrier
+    if (kv0 > qw0 + 31 || qw0 >= len) {
+      wait_loads();
+      __syncthreads();
+      continue;
     }
-    // ---- stage V tile [64][HD] row-major as well; the transposition happens in the fragment reads ----
-#pragma unroll
-    for (int i = 0; i < KITER; ++i) {
-      const int c = tid + i * kAttThreads;
-      const int r = c / CPR, ch = c % CPR;
-      st16(vs + r * VS + ch * 8, vreg[i]);
-    }
-    fetch(min(kv0 + kAttKV, (n_tiles - 1) * kAttKV));  // next tile (the last iteration re-fetches its own)
-    __syncthreads();
-    // every key of this tile is in the future of this wave's queries, or the wave has no query at all
-    if (kv0 > qw0 + 31 || qw0 >= len) continue;
 
     // ---- S^T = K Q^T : two 32-key row tiles ----
     // The two row tiles advance together, so that consecutive matrix instructions write different
@@ -139,21 +142,22 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
       for (int r = 0; r < 16; ++r) sacc[u][r] = 0.f;
     {
       constexpr int HS = DSTEPS / 2;
-      const uint16_t* kr0 = ks + lq * KS + hl * 8;
-      const uint16_t* kr1 = kr0 + 32 * KS;
+      const uint16_t* kr0 = ks + lq * HD;   // chunk 2 st + hl of rows lq and 32 + lq (same swizzle key)
+      const uint16_t* kr1 = kr0 + 32 * HD;
+      auto kcol = [&](int st) { return ((2 * st + hl) ^ kswz) * 8; };
       bf16x8 kf[2][HS];
 #pragma unroll
       for (int st = 0; st < HS; ++st) {
-        kf[0][st] = *reinterpret_cast<const bf16x8*>(kr0 + st * 16);
-        kf[1][st] = *reinterpret_cast<const bf16x8*>(kr1 + st * 16);
+        kf[0][st] = *reinterpret_cast<const bf16x8*>(kr0 + kcol(st));
+        kf[1][st] = *reinterpret_cast<const bf16x8*>(kr1 + kcol(st));
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int st = 0; st < HS; ++st) {
         sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][st], qf[st], sacc[0], 0, 0, 0);
         sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][st], qf[st], sacc[1], 0, 0, 0);
-        kf[0][st] = *reinterpret_cast<const bf16x8*>(kr0 + (st + HS) * 16);
-        kf[1][st] = *reinterpret_cast<const bf16x8*>(kr1 + (st + HS) * 16);
+        kf[0][st] = *reinterpret_cast<const bf16x8*>(kr0 + kcol(st + HS));
+        kf[1][st] = *reinterpret_cast<const bf16x8*>(kr1 + kcol(st + HS));
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
@@ -210,24 +214,29 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
     // lanes, lane j hands in the address of 4 consecutive d of key j / 4 (16 d in all, 4 keys), and lane i
     // gets back the 4 keys at d = i.  Groups 0, 1 serve d 0..15, 16..31 of key group hl = 0, groups 2, 3 of hl = 1.
     const int i16 = lane & 15;
-    const uint16_t* vfrag = vs + (4 * hl + (i16 >> 2)) * VS + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+    const int vswz = CPR == 16 ? ((i16 >> 2) << 2) : (((i16 >> 3) & 1) << 2);   // rows are 4 hl + i16/4 + multiples of 8
+    const uint16_t* vfrag = vs + (4 * hl + (i16 >> 2)) * HD + (i16 & 1) * 4;
+    const int vchunk = 2 * ((lane >> 4) & 1) + ((i16 & 3) >> 1);                 // + 4 d: 16-byte chunk of this lane's 4 d
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int vv = 0; vv < 2; ++vv) {
-        const uint16_t* vstep = vfrag + (u * 32 + vv * 16) * VS;
+        const uint16_t* vstep = vfrag + (u * 32 + vv * 16) * HD;
 #pragma unroll
         for (int d = 0; d < DT; ++d) {
           typedef short short4v __attribute__((ext_vector_type(4)));
           typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
-          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vstep + d * 32));
-          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vstep + 8 * VS + d * 32));
+          const int col = ((4 * d + vchunk) ^ vswz) * 8;
+          const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vstep + col));
+          const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vstep + 8 * HD + col));
           u32x4 packed;
           const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
           packed[0] = l2[0]; packed[1] = l2[1]; packed[2] = h2[0]; packed[3] = h2[1];
           oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, packed), pf[2 * u + vv], oacc[d], 0, 0, 0);
         }
       }
+    wait_loads();     // this wave's share of tile i+1 has landed
+    __syncthreads();  // ... and everybody's; and every wave is done reading tile i
   }
 
   // ---- normalise and store: lane holds O[my_q][32d + 8g + 4hl + i] ----
@@ -264,12 +273,21 @@ hipError_t launch_prefill_attention(const void* q, const void* k, const void* v,
   // all resident at once (two workgroups per compute unit, 256 units) or close to it: balance; else locality
   const int qt_fast = g_attn_force_order >= 0 ? g_attn_force_order : (wgs > 2 * 512 ? 1 : 0);
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
+  // two buffers of [64 K rows | 64 V rows] of head_dim bf16
+  const size_t lds_bytes = (size_t)2 * 2 * kAttKV * head_dim * sizeof(uint16_t);
   if (head_dim == 128) {
-    hipLaunchKernelGGL(prefill_attention_kernel<128>, grid, dim3(kAttThreads), 0, stream, (const uint16_t*)q,
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_attention_kernel<128>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(prefill_attention_kernel<128>, grid, dim3(kAttThreads), lds_bytes, stream, (const uint16_t*)q,
                        (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, kv_group, scale_log2e,
                        (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast);
   } else if (head_dim == 64) {
-    hipLaunchKernelGGL(prefill_attention_kernel<64>, grid, dim3(kAttThreads), 0, stream, (const uint16_t*)q,
+    hipLaunchKernelGGL(prefill_attention_kernel<64>, grid, dim3(kAttThreads), lds_bytes, stream, (const uint16_t*)q,
                        (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, kv_group, scale_log2e,
                        (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast);
   } else {
