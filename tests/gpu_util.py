@@ -46,9 +46,12 @@ def workspace(nbytes: int) -> torch.Tensor:
 def update_ok(y_gpu: np.ndarray, y_ref: np.ndarray, x_in: np.ndarray) -> bool:
     """Gate on the layer's own contribution y - x (the residual input dominates y, so this is the
     sharper check of attention + FFN).  The residual stream is rounded to bf16 twice on the GPU
-    (x1 and y), each within 2^-9 of its magnitude; on top of that the update gets the 1e-2 budget."""
+    (x1 and y), each within half a unit in the last place of its magnitude - for |v| in [2^e, 2^(e+1)) that is
+    2^(e-8), between 2^-9 |v| and 2^-8 |v| - taken at the largest magnitude; on top of that the update gets the
+    1e-2 budget."""
     upd_ref = y_ref - x_in
-    bound = 2 * 2.0 ** -9 * np.max(np.abs(y_ref)) + 1e-2 * np.max(np.abs(upd_ref))
+    half_ulp = 2.0 ** (np.floor(np.log2(np.max(np.abs(y_ref)))) - 8)
+    bound = 2 * half_ulp + 1e-2 * np.max(np.abs(upd_ref))
     return bool(np.max(np.abs((y_gpu - x_in) - upd_ref)) <= bound)
 
 
