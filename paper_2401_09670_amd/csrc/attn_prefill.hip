@@ -88,24 +88,43 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
   // Tile i+1 is requested (global -> LDS, no registers) into the other buffer before tile i is multiplied; one
   // workgroup barrier per tile: it closes the reads of tile i and publishes tile i+1.
   constexpr int NLD = kAttKV * CPR / kAttThreads;   // wave-level loads per wave, tile and operand (4 or 2)
-  int ld_row[NLD], ld_kcol[NLD], ld_vcol[NLD];      // this lane's tile row and (swizzled) source column of load j
+  constexpr int RPL = 64 / CPR;                     // tile rows per wave-level load (4 or 8)
+  // Wave-level load j of a wave drops 64 consecutive 16-byte pieces: tile rows ld_row0 + j RPL .. + RPL - 1 with
+  // all their chunks; the lane's piece is chunk ld_c of its row and comes from source chunk ld_c ^ swizzle(row).
+  // With the row numbers written out the K swizzle is (low bits of the lane's row) ^ 4j, the V swizzle the same for
+  // all j.  A tile that lies inside the request is fetched from one scalar base plus 32-bit lane offsets that do not
+  // change from tile to tile; only the last tile needs its rows clamped.
+  const int ld_sub = lane / CPR, ld_c = lane % CPR;
+  const int ld_row0 = wave * NLD * RPL + ld_sub;
+  const int ld_kcol0 = (ld_c ^ (CPR == 16 ? ld_sub : (ld_sub >> 1))) * 8;
+  const int ld_vcol = (ld_c ^ (CPR == 16 ? (ld_sub << 2) : (((ld_sub >> 1) & 1) << 2))) * 8;
+  uint32_t ld_koff[NLD], ld_voff[NLD];   // element offsets from the tile's first row
 #pragma unroll
   for (int j = 0; j < NLD; ++j) {
-    const int piece = (wave * NLD + j) * 64 + lane;  // 16-byte piece of the tile this lane's data lands in
-    const int r = piece / CPR, c = piece % CPR;
-    ld_row[j] = r;
-    ld_kcol[j] = (c ^ (CPR == 16 ? (r & 15) : ((r >> 1) & 7))) * 8;
-    ld_vcol[j] = (c ^ (CPR == 16 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2))) * 8;
+    ld_koff[j] = (uint32_t)(ld_row0 + j * RPL) * (uint32_t)hk + (uint32_t)(ld_kcol0 ^ (32 * j));
+    ld_voff[j] = (uint32_t)(ld_row0 + j * RPL) * (uint32_t)hk + (uint32_t)ld_vcol;
   }
-  auto request = [&](int kv0, int buf) {  // rows past the end repeat the last key (they are masked out below)
+  auto request = [&](int kv0, int buf) {
     uint16_t* kdst = att_lds + buf * BUF_ELEMS + (wave * NLD) * 512;
+    if (kv0 + kAttKV <= len) {
+      const uint16_t* kt = kbase + (size_t)kv0 * hk;
+      const uint16_t* vt = vbase + (size_t)kv0 * hk;
 #pragma unroll
-    for (int j = 0; j < NLD; ++j) {
-      const size_t row = (size_t)min(kv0 + ld_row[j], len - 1) * hk;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + row + ld_kcol[j]),
-                                       (__attribute__((address_space(3))) void*)(kdst + j * 512), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + row + ld_vcol[j]),
-                                       (__attribute__((address_space(3))) void*)(kdst + TILE_ELEMS + j * 512), 16, 0, 0);
+      for (int j = 0; j < NLD; ++j) {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kt + ld_koff[j]),
+                                         (__attribute__((address_space(3))) void*)(kdst + j * 512), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vt + ld_voff[j]),
+                                         (__attribute__((address_space(3))) void*)(kdst + TILE_ELEMS + j * 512), 16, 0, 0);
+      }
+    } else {   // rows past the end repeat the last key (they are masked out below)
+#pragma unroll
+      for (int j = 0; j < NLD; ++j) {
+        const size_t row = (size_t)min(kv0 + ld_row0 + j * RPL, len - 1) * hk;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + row + (ld_kcol0 ^ (32 * j))),
+                                         (__attribute__((address_space(3))) void*)(kdst + j * 512), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + row + ld_vcol),
+                                         (__attribute__((address_space(3))) void*)(kdst + TILE_ELEMS + j * 512), 16, 0, 0);
+      }
     }
   };
   auto wait_loads = [] {  // s_waitcnt vmcnt(0) only: vmcnt[3:0] | expcnt=7 | lgkmcnt=15 | vmcnt[5:4] in bits 15:14
@@ -197,15 +216,24 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
         for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
     }
     const float mb = m_run * scale_log2e;
+    // Two probabilities at a time: exponentials, one bf16 pair, and the pair's sum added to the running sum by a
+    // dot product with (1, 1) - the sum then counts exactly the rounded values the second product multiplies.
     float psum = 0.f;
-    bf16x8 pf[4];  // pf[2u+v]: column operand of PV step (u,v)
+    u32x4 pw[4];  // pw[2u+v]: column operand of PV step (u,v), as bf16 pairs
+    bf16x2 ones;
+    ones[0] = (__bf16)1.f;
+    ones[1] = (__bf16)1.f;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pv = __builtin_amdgcn_exp2f(sacc[u][r] * scale_log2e - mb);
-        psum += pv;
-        pf[2 * u + (r >> 3)][r & 7] = (__bf16)pv;
+      for (int r = 0; r < 16; r += 2) {
+        const float pa = __builtin_amdgcn_exp2f(sacc[u][r] * scale_log2e - mb);
+        const float pb = __builtin_amdgcn_exp2f(sacc[u][r + 1] * scale_log2e - mb);
+        bf16x2 pr;
+        pr[0] = (__bf16)pa;
+        pr[1] = (__bf16)pb;
+        psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+        pw[2 * u + (r >> 3)][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, pr);
       }
     l_run += psum;
 
@@ -232,7 +260,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
           u32x4 packed;
           const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
           packed[0] = l2[0]; packed[1] = l2[1]; packed[2] = h2[0]; packed[3] = h2[1];
-          oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, packed), pf[2 * u + vv], oacc[d], 0, 0, 0);
+          oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, packed), __builtin_bit_cast(bf16x8, pw[2 * u + vv]), oacc[d], 0, 0, 0);
         }
       }
     wait_loads();     // this wave's share of tile i+1 has landed
