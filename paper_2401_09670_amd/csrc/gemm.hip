@@ -128,33 +128,41 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   const int kt_first = EPI == kEpiPartial ? (int)blockIdx.y : 0;
   const int KT = (K / kBK - kt_first + kt_step - 1) / kt_step;  // >= 1: splits <= K / 64
 
-  // per-lane source offsets (elements) of this wave's loads; load j covers rows 8*(4j+wave) .. +7
+  // per-lane source offsets (bytes, from the tile's first row) of this wave's loads; load j covers rows
+  // 8*(4j+wave) .. +7.  With the tile origin and the k position in a scalar base, the lane part is a 32-bit
+  // value that never changes, and a load needs no vector arithmetic at all.
   const int lrow = lane >> 3;
   const int lchunk = (lane & 7) ^ (4 * (wave & 1) + (lane >> 4));  // key = (row >> 1) & 7, row = 8*(4j+wave) + lane/8
+  const char* xbase = reinterpret_cast<const char*>(p.X + (size_t)m0 * p.ldx);
+  const char* wbase = reinterpret_cast<const char*>(p.W + (size_t)n0 * K);
   uint32_t xoff[XL], woff[WL];
 #pragma unroll
   for (int j = 0; j < XL; ++j) {
-    const int row = min(m0 + 8 * (4 * j + wave) + lrow, p.M - 1);
-    xoff[j] = (uint32_t)row * (uint32_t)p.ldx + lchunk * 8;
+    const int row = min(8 * (4 * j + wave) + lrow, p.M - 1 - m0);
+    xoff[j] = ((uint32_t)row * (uint32_t)p.ldx + lchunk * 8) * 2u;
   }
 #pragma unroll
   for (int j = 0; j < WL; ++j) {
-    const int row = min(n0 + 8 * (4 * j + wave) + lrow, p.N - 1);
-    woff[j] = (uint32_t)row * (uint32_t)K + lchunk * 8;
+    const int row = min(8 * (4 * j + wave) + lrow, p.N - 1 - n0);
+    woff[j] = ((uint32_t)row * (uint32_t)K + lchunk * 8) * 2u;
   }
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);  // keep LDS destinations in scalar registers
   // Loads k-tile `kt_load` into buffer `stage`.  Tiles past the end are clamped to the last one (a
   // harmless re-load into a buffer nobody reads again): this keeps the main loop free of branches, so
   // the loads can be interleaved with MFMAs by the scheduler.
   auto issue_one = [&](int stage, int kt_load, int j) {   // j in [0, LPS): X loads first, then W loads
-    const int kofs = (kt_first + min(kt_load, KT - 1) * kt_step) * kBK;
+    const size_t kofs = (size_t)((kt_first + min(kt_load, KT - 1) * kt_step) * kBK) * 2;   // bytes
     uint16_t* xb = lds + stage * STAGE_ELEMS + wave_s * 512;     // 512 elements = 1 KB per wave-load
+    // (the empty asm keeps the 32-bit lane offset a value of this basic block: hoisted out of the loop as a
+    // 64-bit pair it costs a 64-bit vector add per load instead of riding in the instruction's offset operand)
+    uint32_t& off = j < XL ? xoff[j < XL ? j : 0] : woff[j < XL ? 0 : j - XL];
+    asm volatile("" : "+v"(off));
     if (j < XL) {
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.X + kofs + xoff[j]),
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xbase + kofs + off),
                                        (__attribute__((address_space(3))) void*)(xb + j * 2048), 16, 0, 0);
     } else {
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(p.W + kofs + woff[j - XL]),
+          (const __attribute__((address_space(1))) void*)(wbase + kofs + off),
           (__attribute__((address_space(3))) void*)(xb + BM * kBK + (j - XL) * 2048), 16, 0, 0);
     }
   };
@@ -174,11 +182,16 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   // swizzled fragment offsets (elements) inside a row, one per k-step
   const int frag_row = lane & 31;
   const int hl = lane >> 5;
-  int koff[kBK / 16];
+  // Kept in registers across the k loop, one per k-step and operand (the empty asm stops the compiler from
+  // recomputing them in the loop): a fragment read is then one add of the stage's base plus an immediate.
+  int xfrag[kBK / 16], wfrag[kBK / 16];
 #pragma unroll
-  for (int kk = 0; kk < kBK / 16; ++kk) koff[kk] = (((2 * kk + hl) ^ ((lane >> 1) & 7)) * 8);
-  const int xrow0 = (wm * WTM + frag_row) * kBK;
-  const int wrow0 = BM * kBK + (wn * WTN + frag_row) * kBK;
+  for (int kk = 0; kk < kBK / 16; ++kk) {
+    const int koff = ((2 * kk + hl) ^ ((lane >> 1) & 7)) * 8;
+    xfrag[kk] = (wm * WTM + frag_row) * kBK + koff;
+    wfrag[kk] = BM * kBK + (wn * WTN + frag_row) * kBK + koff;
+    asm volatile("" : "+v"(xfrag[kk]), "+v"(wfrag[kk]));
+  }
 
   // A k-tile (4 MFMA k-steps) is multiplied in two halves of two k-steps each.  Within a half every
   // accumulator tile gets its two MFMAs back to back (the second one chains on the first one's
@@ -195,8 +208,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   // read number r of the half starting at k-step kk0 of stage buffer sb
   auto frag_read = [&](Frags& f, const uint16_t* sb, int kk0, int r) {
     const int s2 = r / (TN + TM), q = r % (TN + TM);
-    if (q < TN) f.w[s2][q] = *reinterpret_cast<const u32x4*>(sb + wrow0 + q * 32 * kBK + koff[kk0 + s2]);
-    else f.x[s2][q - TN] = *reinterpret_cast<const u32x4*>(sb + xrow0 + (q - TN) * 32 * kBK + koff[kk0 + s2]);
+    if (q < TN) f.w[s2][q] = *reinterpret_cast<const u32x4*>(sb + wfrag[kk0 + s2] + q * 32 * kBK);
+    else f.x[s2][q - TN] = *reinterpret_cast<const u32x4*>(sb + xfrag[kk0 + s2] + (q - TN) * 32 * kBK);
   };
 
   // One half: after each accumulator's MFMA pair the code issues a share of the next half's fragment
