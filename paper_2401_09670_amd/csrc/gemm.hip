@@ -517,27 +517,38 @@ static GemmPlan gemm_plan(int M, int N, int K) {
 
 // Tile quantisation: a launch takes whole rounds of 256 workgroups, so 2.5 rounds cost 3.  Where it pays, the
 // product is cut at a column: the leading n1 columns keep the large tile and fill their rounds (nearly)
-// completely, the remaining ones take 128x128 tiles, whose last round wastes a quarter as much.  Returns n1, or
-// 0 to leave the launch whole.  Costs in the units of tile_cost.
+// completely, the remaining ones go to a second launch on a smaller tile - 256x160 behind 256x256, or 128x128,
+// whose last round wastes a quarter as much - whichever the round count makes cheaper.  n1 = 0 leaves the launch
+// whole.  A round's cost is the tile area times a factor measured at K = 5120 (132.9 / 88.4 / 54.9 us per round
+// of 256x256 / 256x160 / 128x128 tiles: the smaller the tile, the more operand traffic per flop).
 DS_SWITCH(g_gemm_tail_split, 1);  // 0 = never cut a product at a column
-static int tail_split_columns(int M, int N, int variant) {
-  if (!g_gemm_tail_split || (variant != 1 && variant != 3)) return 0;
+DS_SWITCH(g_gemm_tail_kind, -1);  // 0 / 1 force the 128x128 / 256x160 tile for the remainder, -1 choose by cost
+struct TailCut {
+  int n1;     // columns of the first launch (0: no cut)
+  int kind;   // tile of the second launch: 0 = 128x128, 1 = 256x160
+};
+static TailCut tail_split_columns(int M, int N, int variant) {
+  if (!g_gemm_tail_split || (variant != 1 && variant != 3)) return {0, 0};
   const int bm = 256, bn = variant == 1 ? 160 : 256;
-  const double big = bm * bn * (variant == 1 ? 1.0 : 0.9), small = 128 * 128 * 1.3;
+  const double big = bm * bn * (variant == 1 ? 1.0 : 0.94), mid = 256 * 160 * 1.0, small = 128 * 128 * 1.55;
   const long tm = (M + bm - 1) / bm, tn = (N + bn - 1) / bn, tm2 = (M + 127) / 128;
   const double whole = (double)((tm * tn + 255) / 256) * big;
   double best = whole;
-  int best_c = 0;
-  for (long c = 1; c < tn; ++c) {
+  TailCut cut = {0, 0};
+  for (long c = tn - 1; c >= 1; --c) {   // among equal costs the longest head wins
     const long rest = N - c * bn;
-    if (rest <= 0) break;
-    const double cost = (double)((tm * c + 255) / 256) * big + (double)((tm2 * ((rest + 127) / 128) + 255) / 256) * small;
+    if (rest <= 0) continue;
+    const double head = (double)((tm * c + 255) / 256) * big;
+    const double tail128 = (double)((tm2 * ((rest + 127) / 128) + 255) / 256) * small;
+    const double tail160 = (double)((tm * ((rest + 159) / 160) + 255) / 256) * mid;
+    const bool use160 = g_gemm_tail_kind < 0 ? (variant == 3 && tail160 < tail128) : g_gemm_tail_kind == 1;
+    const double cost = head + (use160 ? tail160 : tail128);
     if (cost < best) {
       best = cost;
-      best_c = (int)c;
+      cut = {(int)(c * bn), use160 ? 1 : 0};
     }
   }
-  return best < 0.95 * whole ? best_c * bn : 0;  // a second launch has to earn its ramp-up
+  return best < 0.95 * whole ? cut : TailCut{0, 0};  // a second launch has to earn its ramp-up
 }
 
 int gemm_splits(int M, int N, int K) {
@@ -599,17 +610,18 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
     if (fused_done) *fused_done = true;
   }
   hipError_t e;
-  const int n1 = (pl.splits == 1 && !p.k_cache) ? tail_split_columns(M, N, pl.variant) : 0;
-  if (n1 > 0) {
-    // Leading columns on the large tile in (nearly) whole rounds of 256 workgroups, the rest on 128x128 tiles:
+  const TailCut cut = (pl.splits == 1 && !p.k_cache) ? tail_split_columns(M, N, pl.variant) : TailCut{0, 0};
+  if (cut.n1 > 0) {
+    // Leading columns on the large tile in (nearly) whole rounds of 256 workgroups, the rest on a smaller tile:
     // two launches over disjoint column ranges [0, n1) and [n1, N) of the same product (same operands, bias,
     // residual and output segments; only the column range differs).
     GemmParams a = p, b = p;
-    a.N = n1;
-    b.n_base = n1;
+    a.N = cut.n1;
+    b.n_base = cut.n1;
     e = pl.variant == 3 ? launch_dl<256, 256, 2, 2, 2, false>(a, 1, stream)
                         : launch_dl<256, 160, 4, 1, 3, false>(a, 1, stream);
     if (e != hipSuccess) return e;
+    if (cut.kind == 1) return launch_dl<256, 160, 4, 1, 3, false>(b, 1, stream);
     return launch_dl<128, 128, 2, 2, 3, true>(b, 1, stream);
   }
   switch (pl.variant) {
