@@ -22,14 +22,21 @@
  *     default stream); no call synchronises; outputs are valid once the
  *     caller has synchronised the stream.
  *   - Calls record kernel launches only (no allocation, host copy or memset), so a
- *     sequence of calls can be captured into a HIP graph; the first launch of a
- *     kernel configuration sets a function attribute, so run the sequence once
- *     eagerly before capturing it.  A context is not thread-safe: one thread at a
- *     time per ds_ctx.
+ *     sequence of calls can be captured into a HIP graph.  Kernel attributes are
+ *     set once per device by ds_create (or by the first call on a device the
+ *     context was not created on), never on a launch path.  A context is not
+ *     thread-safe: one thread at a time per ds_ctx.
  *   - Errors are returned as ds_status; arguments are checked on the host
  *     before anything is launched.  Contents of device index arrays
- *     (cu_seqlens, block_tables, ctx_lens) are NOT validated: out-of-range
- *     entries are the caller's responsibility.  ds_last_error() gives text.
+ *     (cu_seqlens, block_tables, ctx_lens / kv_lens) are NOT validated by default
+ *     (that needs a copy to the host and a stream synchronisation): out-of-range
+ *     entries are the caller's responsibility, and a max_ctx / max_seqlen bound
+ *     smaller than a real length silently drops the excess tokens.  The debug
+ *     path - DS_DEBUG_VALIDATE=1 in the environment when the context is created,
+ *     or ds_set_validate(ctx, 1) - copies these arrays back before launching and
+ *     returns DS_ERR_BOUNDS naming the first offending entry; it synchronises the
+ *     stream, so it must not be used under graph capture.  ds_last_error() gives
+ *     text.
  *   - Paged cache layout: k_cache, v_cache [num_blocks, n, block_size, s] bf16.
  *     Token j of sequence i lives in block block_tables[i*max_blocks + j/bs],
  *     slot j % bs.  Unused table entries are -1 and never dereferenced.
@@ -49,7 +56,8 @@ typedef enum {
   DS_ERR_INVALID_ARG = 1, /* NULL / non-positive size / misaligned pointer / inconsistent sizes */
   DS_ERR_UNSUPPORTED = 2, /* a shape this build has no kernel for */
   DS_ERR_WORKSPACE = 3,   /* workspace smaller than ds_*_workspace_bytes() */
-  DS_ERR_HIP = 4          /* a HIP runtime call or launch failed */
+  DS_ERR_HIP = 4,         /* a HIP runtime call or launch failed */
+  DS_ERR_BOUNDS = 5       /* debug validation: an entry of a device index array is out of range */
 } ds_status;
 
 /* Layer dimensions.  Supported: head_dim in {64,128}; hidden = n_heads*head_dim;
@@ -87,6 +95,12 @@ ds_status ds_create(const ds_model_cfg *cfg, ds_ctx **out);
 void ds_destroy(ds_ctx *ctx);
 /* Text of the last error recorded on ctx (never NULL). */
 const char *ds_last_error(const ds_ctx *ctx);
+/* Turn the debug validation of device index arrays on / off (see the conventions above).  When on,
+ * ds_prefill, ds_prefill_attention and ds_kv_migrate check cu_seqlens (starts at 0, ends at t, every
+ * length in [1, max_seqlen]); ds_kv_migrate, ds_decode_step and ds_decode_attention check that every
+ * page a sequence's tokens need is named in block_tables with an id in [0, num_blocks), and that
+ * ctx_lens[i] + 1 lies in [1, max_ctx] (kv_lens[i] in [0, max_kv_len]). */
+ds_status ds_set_validate(ds_ctx *ctx, int32_t on);
 
 /* Workspace (device bytes) ds_prefill needs for up to max_tokens packed tokens.
  * Both sizes are upper bounds over all smaller calls: a workspace sized for the
@@ -197,7 +211,8 @@ ds_status ds_prefill_attention(ds_ctx *ctx, const void *q, const void *k, const 
 
 /* One-query attention over the paged cache: sequence i attends over its first
  * kv_lens[i] cached tokens (App. A.3).  q,o device [B,n,s]; max_kv_len is a host
- * bound of kv_lens; workspace of ds_decode_workspace_bytes(B, max_kv_len). */
+ * bound of kv_lens; workspace of ds_decode_workspace_bytes(B, max_kv_len).  A sequence
+ * with kv_lens[i] = 0 has nothing to attend over: its output rows are 0. */
 ds_status ds_decode_attention(ds_ctx *ctx, const void *q, const int32_t *kv_lens,
                               const int32_t *block_tables, int32_t B, int32_t max_blocks_per_seq,
                               int32_t max_kv_len, const void *k_cache, const void *v_cache,

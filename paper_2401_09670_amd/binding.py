@@ -17,12 +17,12 @@ LIB_PATH = os.path.join(PKG_DIR, "libds.so")
 
 DS_OK = 0
 STATUS_NAMES = {0: "DS_OK", 1: "DS_ERR_INVALID_ARG", 2: "DS_ERR_UNSUPPORTED", 3: "DS_ERR_WORKSPACE",
-                4: "DS_ERR_HIP"}
+                4: "DS_ERR_HIP", 5: "DS_ERR_BOUNDS"}
 KERNEL_CLASSES = ("layernorm", "gemm", "prefill_attn", "kv_migrate", "skinny_gemm", "decode_attn", "kv_append",
                   "token_io")
 
 # every symbol include/ds.h declares
-EXPORTS = ("ds_create", "ds_destroy", "ds_last_error", "ds_prefill_workspace_bytes",
+EXPORTS = ("ds_create", "ds_destroy", "ds_last_error", "ds_set_validate", "ds_prefill_workspace_bytes",
            "ds_decode_workspace_bytes", "ds_prefill", "ds_kv_migrate", "ds_decode_step", "ds_layernorm",
            "ds_linear_workspace_bytes", "ds_linear", "ds_prefill_attention", "ds_decode_attention",
            "ds_embed", "ds_next_token_workspace_bytes", "ds_next_token", "ds_profile_enable", "ds_profile_collect")
@@ -65,6 +65,8 @@ def load_library() -> ctypes.CDLL:
     lib.ds_destroy.restype = None
     lib.ds_last_error.argtypes = [vp]
     lib.ds_last_error.restype = ctypes.c_char_p
+    lib.ds_set_validate.argtypes = [vp, i32]
+    lib.ds_set_validate.restype = ctypes.c_int
     lib.ds_prefill_workspace_bytes.argtypes = [vp, i32]
     lib.ds_prefill_workspace_bytes.restype = sz
     lib.ds_decode_workspace_bytes.argtypes = [vp, i32, i32]
@@ -152,6 +154,9 @@ class Context:
         for name, _ in LayerWeights._fields_:
             setattr(lw, name, _ptr(w.get(name)))
         return lw, w
+
+    def ds_set_validate(self, on: bool):
+        self._check(self.lib.ds_set_validate(self.handle, 1 if on else 0))
 
     # ---- sizes ----
     def ds_prefill_workspace_bytes(self, max_tokens: int) -> int:

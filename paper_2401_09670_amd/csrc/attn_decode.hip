@@ -168,7 +168,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_attention_kernel(
       }
     }
     if (n_splits == 1) {
-      reinterpret_cast<__bf16*>(o)[((size_t)seq * n_heads + head) * HD + tid] = (__bf16)(a / l);
+      reinterpret_cast<__bf16*>(o)[((size_t)seq * n_heads + head) * HD + tid] = (__bf16)(l > 0.f ? a / l : 0.f);  // no key at all (kv_len = 0): defined as 0
     } else {
       float* dst = partial + (((size_t)seq * n_heads + head) * n_splits + split) * (HD + 2);
       if (tid == 0) {
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(HD) void decode_combine_kernel(const float* __restr
       a += src[s * (HD + 2) + 2 + tid] * f;
     }
   }
-  reinterpret_cast<__bf16*>(o)[item * HD + tid] = (__bf16)(a / l);
+  reinterpret_cast<__bf16*>(o)[item * HD + tid] = (__bf16)(l > 0.f ? a / l : 0.f);  // no key at all (kv_len = 0): defined as 0
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -417,7 +417,7 @@ __global__ __launch_bounds__(kDecThreads) __attribute__((amdgpu_waves_per_eu(2))
     }
     const size_t item = (size_t)seq * n_heads + kv_head * G + h;
     if (n_splits == 1) {
-      const float inv = 1.f / l;
+      const float inv = l > 0.f ? 1.f / l : 0.f;  // no key at all (kv_len = 0): output 0
       u32x4 ov;
 #pragma unroll
       for (int j = 0; j < 4; ++j) ov[j] = pack_bf16(a[2 * j] * inv, a[2 * j + 1] * inv);

@@ -304,13 +304,7 @@ hipError_t launch_prefill_attention(const void* q, const void* k, const void* v,
   // two buffers of [64 K rows | 64 V rows] of head_dim bf16
   const size_t lds_bytes = (size_t)2 * 2 * kAttKV * head_dim * sizeof(uint16_t);
   if (head_dim == 128) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_attention_kernel<128>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
+    (void)KernelAttrReg<prefill_attention_kernel<128>, 2 * 2 * kAttKV * 128 * (int)sizeof(uint16_t)>::done;
     hipLaunchKernelGGL(prefill_attention_kernel<128>, grid, dim3(kAttThreads), lds_bytes, stream, (const uint16_t*)q,
                        (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, kv_group, scale_log2e,
                        (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast);

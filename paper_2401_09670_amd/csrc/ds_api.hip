@@ -5,8 +5,10 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -18,6 +20,7 @@ struct ds_ctx {
   ds_model_cfg cfg;  // n_kv_heads is normalised at creation: always the actual count, never 0
   char err[512];
   bool profile;
+  bool validate;  // copy the index arrays back and check them before launching (debug path)
   struct Rec {
     int kind;
     hipEvent_t a, b;
@@ -30,7 +33,56 @@ struct ds_ctx {
   mutable std::map<std::pair<int, int>, size_t> decode_ws;
 };
 
+// ---- per-device set-up: kernel attributes ----
+namespace ds {
 namespace {
+std::vector<std::pair<const void*, int>>& attr_list() {
+  static std::vector<std::pair<const void*, int>> list;
+  return list;
+}
+}  // namespace
+void register_kernel_attr(const void* fn, int lds_bytes) { attr_list().emplace_back(fn, lds_bytes); }
+hipError_t configure_kernels() {
+  for (const auto& a : attr_list()) {
+    const hipError_t e = hipFuncSetAttribute(a.first, hipFuncAttributeMaxDynamicSharedMemorySize, a.second);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+}  // namespace ds
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+struct DeviceState {
+  bool ready = false;
+};
+std::mutex g_dev_mu;
+DeviceState g_dev[kMaxDevices];
+
+// Once per device, with that device current: function attributes of every kernel.  Returns the device's
+// state, or null with *err set.
+const DeviceState* device_state(hipError_t* err) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+  if (e != hipSuccess) {
+    *err = e;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_dev_mu);
+  DeviceState& st = g_dev[dev];
+  if (!st.ready) {
+    e = ds::configure_kernels();
+    if (e != hipSuccess) {
+      *err = e;
+      return nullptr;
+    }
+    st.ready = true;
+  }
+  *err = hipSuccess;
+  return &st;
+}
 
 constexpr int kSkinnyMaxRows = 256;
 
@@ -62,7 +114,13 @@ struct Timed {
     if (!ctx->profile) return;
     a = take();
     b = take();
-    if (a && b) (void)hipEventRecord(a, stream);
+    if (a && b) {
+      (void)hipEventRecord(a, stream);
+    } else {  // no timing for this launch; an event that was obtained goes back to the pool
+      if (a) ctx->pool.push_back(a);
+      if (b) ctx->pool.push_back(b);
+      a = b = nullptr;
+    }
   }
   ~Timed() {
     if (!ctx->profile || !a || !b) return;
@@ -157,6 +215,77 @@ size_t max_gemm_ws(const ds_model_cfg& c, int rows) {
   return m > e ? m : e;
 }
 
+// Every call that launches goes through here first: the device's one-time set-up (normally done by ds_create;
+// repeated here for a context that is used on another device than it was created on).
+ds_status ensure_device(ds_ctx* ctx, const DeviceState** out = nullptr) {
+  hipError_t e;
+  const DeviceState* st = device_state(&e);
+  if (!st) return fail(ctx, DS_ERR_HIP, "device set-up failed: %s", hipGetErrorString(e));
+  if (out) *out = st;
+  return DS_OK;
+}
+
+// ---- debug validation of device index arrays (ctx->validate) ----
+ds_status fetch_i32(ds_ctx* ctx, const int32_t* dev, size_t n, hipStream_t s, std::vector<int32_t>& out) {
+  out.resize(n);
+  hipError_t e = hipMemcpyAsync(out.data(), dev, n * sizeof(int32_t), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return fail(ctx, DS_ERR_HIP, "validation copy failed: %s", hipGetErrorString(e));
+  return DS_OK;
+}
+
+// cu_seqlens [B+1]: starts at 0, ends at t, every length in [1, max_seqlen]
+ds_status validate_cu(ds_ctx* ctx, const char* who, const int32_t* cu_dev, int B, int t, int max_seqlen,
+                      hipStream_t s, std::vector<int32_t>& cu) {
+  ds_status st = fetch_i32(ctx, cu_dev, (size_t)B + 1, s, cu);
+  if (st != DS_OK) return st;
+  if (cu[0] != 0) return fail(ctx, DS_ERR_BOUNDS, "%s: cu_seqlens[0] = %d, must be 0", who, cu[0]);
+  for (int i = 0; i < B; ++i) {
+    const long len = (long)cu[i + 1] - cu[i];
+    if (len < 1) return fail(ctx, DS_ERR_BOUNDS, "%s: cu_seqlens not increasing at sequence %d", who, i);
+    if (len > max_seqlen)
+      return fail(ctx, DS_ERR_BOUNDS, "%s: sequence %d has %ld tokens > max_seqlen %d", who, i, len, max_seqlen);
+  }
+  if (cu[B] != t) return fail(ctx, DS_ERR_BOUNDS, "%s: cu_seqlens[B] = %d, must be t = %d", who, cu[B], t);
+  return DS_OK;
+}
+
+// the first ceil(tokens[i] / page) entries of every row of block_tables name a block in [0, num_blocks)
+ds_status validate_tables(ds_ctx* ctx, const char* who, const int32_t* bt_dev, int B, int max_blocks,
+                          int num_blocks, const std::vector<int32_t>& tokens, hipStream_t s) {
+  std::vector<int32_t> bt;
+  ds_status st = fetch_i32(ctx, bt_dev, (size_t)B * max_blocks, s, bt);
+  if (st != DS_OK) return st;
+  const int page = ctx->cfg.block_size;
+  for (int i = 0; i < B; ++i) {
+    const long pages = ((long)tokens[i] + page - 1) / page;
+    if (pages > max_blocks)
+      return fail(ctx, DS_ERR_BOUNDS, "%s: sequence %d needs %ld pages > max_blocks_per_seq %d", who, i, pages,
+                  max_blocks);
+    for (long j = 0; j < pages; ++j) {
+      const int32_t id = bt[(size_t)i * max_blocks + j];
+      if (id < 0 || id >= num_blocks)
+        return fail(ctx, DS_ERR_BOUNDS, "%s: block_tables[%d][%ld] = %d outside [0, %d)", who, i, j, id, num_blocks);
+    }
+  }
+  return DS_OK;
+}
+
+// lengths [B] of a decode call: lens[i] + add in [lo, bound]; on return `tokens` holds lens[i] + add
+ds_status validate_lens(ds_ctx* ctx, const char* who, const int32_t* lens_dev, int B, int add, int lo, int bound,
+                        hipStream_t s, std::vector<int32_t>& tokens) {
+  ds_status st = fetch_i32(ctx, lens_dev, (size_t)B, s, tokens);
+  if (st != DS_OK) return st;
+  for (int i = 0; i < B; ++i) {
+    const long l = (long)tokens[i] + add;
+    if (l < lo || l > bound)
+      return fail(ctx, DS_ERR_BOUNDS, "%s: sequence %d attends over %ld tokens, outside [%d, %d]", who, i, l, lo,
+                  bound);
+    tokens[i] = (int32_t)l;
+  }
+  return DS_OK;
+}
+
 ds_status check_weights(ds_ctx* ctx, const ds_layer_weights* w) {
   if (!w) return fail(ctx, DS_ERR_INVALID_ARG, "weights is NULL");
   const void* need[] = {w->ln1_g, w->ln1_b, w->w_qkv, w->w_o, w->ln2_g, w->ln2_b, w->w_fc1, w->w_fc2};
@@ -189,9 +318,22 @@ ds_status ds_create(const ds_model_cfg* cfg, ds_ctx** out) {
   c->cfg.n_kv_heads = n_kv;
   c->err[0] = 0;
   c->profile = false;
+  const char* dbg = getenv("DS_DEBUG_VALIDATE");
+  c->validate = dbg && dbg[0] && strcmp(dbg, "0") != 0;
+  // One-time set-up of the current device (kernel attributes).  Without a usable device
+  // the context is still good for the size queries; the first call that launches reports the failure.
+  hipError_t e;
+  (void)device_state(&e);
   *out = c;
   return DS_OK;
 }
+
+ds_status ds_set_validate(ds_ctx* ctx, int32_t on) {
+  if (!ctx) return DS_ERR_INVALID_ARG;
+  ctx->validate = on != 0;
+  return DS_OK;
+}
+
 
 void ds_destroy(ds_ctx* ctx) {
   if (!ctx) return;
@@ -248,6 +390,7 @@ ds_status ds_layernorm(ds_ctx* ctx, const void* x, const void* gamma, const void
   if (!x || !gamma || !beta || !out || rows <= 0) return fail(ctx, DS_ERR_INVALID_ARG, "ds_layernorm: bad argument");
   if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(out))
     return fail(ctx, DS_ERR_INVALID_ARG, "ds_layernorm: pointers must be 16-byte aligned");
+  if (ds_status st = ensure_device(ctx)) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
   DS_LAUNCH(ctx, s, DS_K_LAYERNORM, ds::launch_layernorm(x, gamma, beta, out, rows, ctx->cfg.hidden, ctx->cfg.ln_eps, s));
   return DS_OK;
@@ -272,6 +415,7 @@ ds_status ds_linear(ds_ctx* ctx, const void* x, const void* w, const void* bias,
   const size_t need = ds_linear_workspace_bytes(ctx, rows, in_f, out_f);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(ctx, DS_ERR_WORKSPACE, "ds_linear: workspace %zu < %zu", workspace_bytes, need);
+  if (ds_status st = ensure_device(ctx)) return st;
   ds::Epilogue ep;
   ep.bias = bias;
   ep.residual = residual;
@@ -290,6 +434,7 @@ ds_status ds_embed(ds_ctx* ctx, const int32_t* token_ids, const int32_t* positio
     return fail(ctx, DS_ERR_INVALID_ARG, "ds_embed: a position table needs positions and n_pos > 0");
   if (!aligned16(tok_emb) || !aligned16(pos_emb) || !aligned16(x))
     return fail(ctx, DS_ERR_INVALID_ARG, "ds_embed: tables and x must be 16-byte aligned");
+  if (ds_status st = ensure_device(ctx)) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
   DS_LAUNCH(ctx, s, DS_K_TOKEN_IO,
             ds::launch_embed(token_ids, positions, tok_emb, vocab, pos_emb, n_pos, rows, ctx->cfg.hidden, x, s));
@@ -317,6 +462,7 @@ ds_status ds_next_token(ds_ctx* ctx, const void* x, const int32_t* row_index, in
   const size_t need = ds_next_token_workspace_bytes(ctx, rows, vocab);
   if (!workspace || workspace_bytes < need)
     return fail(ctx, DS_ERR_WORKSPACE, "ds_next_token: workspace %zu < %zu", workspace_bytes, need);
+  if (ds_status st = ensure_device(ctx)) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
   Carver cv(workspace);
   void* a = cv.take((size_t)rows * ctx->cfg.hidden * 2);
@@ -336,7 +482,12 @@ ds_status ds_prefill_attention(ds_ctx* ctx, const void* q, const void* k, const 
     return fail(ctx, DS_ERR_INVALID_ARG, "ds_prefill_attention: bad argument");
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
     return fail(ctx, DS_ERR_INVALID_ARG, "ds_prefill_attention: pointers must be 16-byte aligned");
+  if (ds_status st = ensure_device(ctx)) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (ctx->validate) {
+    std::vector<int32_t> cu;
+    if (ds_status st = validate_cu(ctx, "ds_prefill_attention", cu_seqlens, B, t, max_seqlen, s, cu)) return st;
+  }
   DS_LAUNCH(ctx, s, DS_K_PREFILL_ATTN,
             ds::launch_prefill_attention(q, k, v, cu_seqlens, B, max_seqlen, ctx->cfg.n_heads, ctx->cfg.n_kv_heads,
                                          ctx->cfg.head_dim, o, s));
@@ -359,10 +510,15 @@ ds_status ds_prefill(ds_ctx* ctx, const ds_layer_weights* w, const void* x, cons
   const size_t need = ds_prefill_workspace_bytes(ctx, t);
   if (!workspace || workspace_bytes < need)
     return fail(ctx, DS_ERR_WORKSPACE, "ds_prefill: workspace %zu < %zu", workspace_bytes, need);
+  if ((st = ensure_device(ctx)) != DS_OK) return st;
 
   const ds_model_cfg& c = ctx->cfg;
   const int h = c.hidden, m = c.ffn;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (ctx->validate) {
+    std::vector<int32_t> cu;
+    if ((st = validate_cu(ctx, "ds_prefill", cu_seqlens, B, t, max_seqlen, s, cu)) != DS_OK) return st;
+  }
   Carver ws(workspace);
   void* a = ws.take((size_t)t * h * 2);
   void* q = ws.take((size_t)t * h * 2);
@@ -438,7 +594,15 @@ ds_status ds_kv_migrate(ds_ctx* ctx, const void* k_src, const void* v_src, const
                 max_seqlen, max_blocks_per_seq);
   if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(k_cache) || !aligned16(v_cache))
     return fail(ctx, DS_ERR_INVALID_ARG, "ds_kv_migrate: pointers must be 16-byte aligned");
+  if (ds_status st = ensure_device(ctx)) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (ctx->validate) {
+    std::vector<int32_t> cu, lens((size_t)B);
+    if (ds_status st = validate_cu(ctx, "ds_kv_migrate", cu_seqlens, B, t, max_seqlen, s, cu)) return st;
+    for (int i = 0; i < B; ++i) lens[i] = cu[i + 1] - cu[i];
+    if (ds_status st = validate_tables(ctx, "ds_kv_migrate", block_tables, B, max_blocks_per_seq, num_blocks, lens, s))
+      return st;
+  }
   DS_LAUNCH(ctx, s, DS_K_KV_MIGRATE,
             ds::launch_kv_migrate(k_src, v_src, cu_seqlens, B, max_seqlen, block_tables, max_blocks_per_seq,
                                   k_cache, v_cache, ctx->cfg.n_kv_heads, ctx->cfg.head_dim, s));
@@ -461,7 +625,15 @@ ds_status ds_decode_attention(ds_ctx* ctx, const void* q, const int32_t* kv_lens
   const size_t need = ds::decode_attention_workspace_bytes(B, c.n_heads, c.n_kv_heads, c.head_dim, max_kv_len);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(ctx, DS_ERR_WORKSPACE, "ds_decode_attention: workspace %zu < %zu", workspace_bytes, need);
+  if (ds_status st = ensure_device(ctx)) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (ctx->validate) {
+    std::vector<int32_t> lens;
+    if (ds_status st = validate_lens(ctx, "ds_decode_attention", kv_lens, B, 0, 0, max_kv_len, s, lens)) return st;
+    if (ds_status st = validate_tables(ctx, "ds_decode_attention", block_tables, B, max_blocks_per_seq, num_blocks,
+                                       lens, s))
+      return st;
+  }
   DS_LAUNCH(ctx, s, DS_K_DECODE_ATTN,
             ds::launch_decode_attention(q, c.hidden, kv_lens, 0, block_tables, B, max_blocks_per_seq, max_kv_len,
                                         k_cache, v_cache, c.n_heads, c.n_kv_heads, c.head_dim, o, workspace, s));
@@ -488,10 +660,18 @@ ds_status ds_decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, 
   const size_t need = ds_decode_workspace_bytes(ctx, B, max_ctx);
   if (!workspace || workspace_bytes < need)
     return fail(ctx, DS_ERR_WORKSPACE, "ds_decode_step: workspace %zu < %zu", workspace_bytes, need);
+  if ((st = ensure_device(ctx)) != DS_OK) return st;
 
   const ds_model_cfg& c = ctx->cfg;
   const int h = c.hidden, m = c.ffn;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (ctx->validate) {
+    std::vector<int32_t> lens;
+    if ((st = validate_lens(ctx, "ds_decode_step", ctx_lens, B, 1, 1, max_ctx, s, lens)) != DS_OK) return st;
+    if ((st = validate_tables(ctx, "ds_decode_step", block_tables, B, max_blocks_per_seq, num_blocks, lens, s)) !=
+        DS_OK)
+      return st;
+  }
   Carver ws(workspace);
   void* a = ws.take((size_t)B * h * 2);
   void* o = ws.take((size_t)B * h * 2);
@@ -568,19 +748,27 @@ ds_status ds_profile_collect(ds_ctx* ctx, double* ms, int64_t* launches) {
     ms[i] = 0.0;
     launches[i] = 0;
   }
-  for (auto& r : ctx->recs) {
-    hipError_t e = hipEventSynchronize(r.b);
+  // The record is taken over first, so every event goes back to the pool exactly once whether or not a
+  // timing call fails on the way.
+  std::vector<ds_ctx::Rec> recs;
+  recs.swap(ctx->recs);
+  hipError_t first_err = hipSuccess;
+  for (auto& r : recs) {
     float t = 0.f;
+    hipError_t e = first_err;
+    if (e == hipSuccess) e = hipEventSynchronize(r.b);
     if (e == hipSuccess) e = hipEventElapsedTime(&t, r.a, r.b);
-    if (e != hipSuccess) return fail(ctx, DS_ERR_HIP, "event timing failed: %s", hipGetErrorString(e));
-    if (r.kind >= 0 && r.kind < DS_K_COUNT) {
+    if (e != hipSuccess) {
+      if (first_err == hipSuccess) first_err = e;
+    } else if (r.kind >= 0 && r.kind < DS_K_COUNT) {
       ms[r.kind] += t;
       launches[r.kind] += 1;
     }
     ctx->pool.push_back(r.a);
     ctx->pool.push_back(r.b);
   }
-  ctx->recs.clear();
+  if (first_err != hipSuccess)
+    return fail(ctx, DS_ERR_HIP, "event timing failed: %s", hipGetErrorString(first_err));
   return DS_OK;
 }
 

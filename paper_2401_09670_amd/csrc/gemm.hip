@@ -413,14 +413,8 @@ static hipError_t launch_dl_epi(GemmParams p, int splits, hipStream_t stream) {
   p.tiles_n = (p.N - p.n_base + BN - 1) / BN;
   constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * kBK * sizeof(uint16_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS");
-  auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, EPI>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, EPI>;
+  (void)KernelAttrReg<kern, (int)lds_bytes>::done;
   hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n, splits), dim3(kGemmThreads), lds_bytes, stream, p);
   return hipGetLastError();
 }

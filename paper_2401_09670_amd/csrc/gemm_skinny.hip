@@ -689,14 +689,8 @@ static hipError_t launch_skinny_cfg(const SkinnyParams& p, int splits, hipStream
   static_assert(lds_bytes <= 160 * 1024, "LDS");
   static_assert((size_t)4 * NTW * MT * 64 * 16 + (size_t)4 * MT * 16 * 8 <= lds_bytes,
                 "k-half reduction (and the greedy-choice candidates behind it) fit the stages");
-  auto kern = skinny_gemm_kernel<MT, NTW, S>;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kern = skinny_gemm_kernel<MT, NTW, S>;
+  (void)KernelAttrReg<kern, (int)lds_bytes>::done;
   hipLaunchKernelGGL(kern, dim3((p.N + BN - 1) / BN, splits), dim3(kSkThreads), lds_bytes, stream, p);
   return hipGetLastError();
 }
@@ -705,14 +699,8 @@ template <int NT, int MT, int S, int NW>
 static hipError_t launch_wring_cfg(const SkinnyParams& p, hipStream_t stream) {
   constexpr size_t lds_bytes = (size_t)NW * S * (16 * MT + 16 * NT) * kWrKS * sizeof(uint16_t);  // NW waves x S stages
   static_assert(lds_bytes <= 160 * 1024 && (size_t)NW * NT * MT * 1024 <= lds_bytes, "LDS");
-  auto kern = wring_gemm_kernel<NT, MT, S, NW>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  constexpr auto kern = wring_gemm_kernel<NT, MT, S, NW>;
+  (void)KernelAttrReg<kern, (int)lds_bytes>::done;
   hipLaunchKernelGGL(kern, dim3((p.N + 16 * NT - 1) / (16 * NT)), dim3(64 * NW), lds_bytes, stream, p);
   return hipGetLastError();
 }

@@ -7,6 +7,17 @@
 
 namespace ds {
 
+// Kernels that ask for more dynamic LDS than the default limit need a function attribute on every device they
+// run on.  Each launcher names its (kernel, bytes) pair through KernelAttrReg, which files the pair in a
+// list when the library is loaded; configure_kernels() applies the whole list to the current device.  The
+// C ABI layer calls it once per device (context creation), so no launch path carries set-up state.
+void register_kernel_attr(const void* fn, int lds_bytes);
+hipError_t configure_kernels();
+template <auto Kern, int LdsBytes>
+struct KernelAttrReg {
+  static inline const bool done = (register_kernel_attr(reinterpret_cast<const void*>(Kern), LdsBytes), true);
+};
+
 // y = LN(x) * gamma + beta, one workgroup per row.  h % 8 == 0, h <= 16384.
 // With `row_index` (device, `rows` entries) output row r normalises input row row_index[r].
 hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, void* out,
