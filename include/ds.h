@@ -154,6 +154,25 @@ ds_status ds_decode_step(ds_ctx *ctx, const ds_layer_weights *w, const void *x,
                          void *k_cache, void *v_cache, int32_t num_blocks,
                          void *y, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * ds_decode_step for callers that cannot allocate device memory or carry a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * same results as ds_decode_step, minus the workspace: the step's scratch (activations between its
+ * kernels, split-K and attention partial sums) lives in a static device array of DS_STATIC_SCRATCH_BYTES
+ * that every GPU the library runs on holds until the process ends.  The call allocates and frees nothing.
+ * A step that needs more (ds_decode_workspace_bytes(ctx, B, max_ctx) > DS_STATIC_SCRATCH_BYTES, e.g.
+ * batches beyond ~128 sequences of an OPT-13B layer) is rejected with DS_ERR_WORKSPACE before anything is
+ * launched.  All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different
+ * streams, different threads or contexts) race on it and must be serialised by the caller; nothing in the
+ * array has to survive from one call to the next, and nothing in it has to start out as zero.
+ */
+#define DS_STATIC_SCRATCH_BYTES (32u << 20)
+ds_status ds_decode_step_static(ds_ctx *ctx, const ds_layer_weights *w, const void *x,
+                                const int32_t *ctx_lens, const int32_t *block_tables,
+                                int32_t B, int32_t max_blocks_per_seq, int32_t max_ctx,
+                                void *k_cache, void *v_cache, int32_t num_blocks,
+                                void *y, void *stream);
+
 /* ---- the individual steps, exported for per-kernel parity tests and timing ---- */
 
 /* out[r,:] = LN(x[r,:]) * gamma + beta, rows x h bf16 (App. A: LayerNorm is a

@@ -16,6 +16,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG_DIR, "libds.so")
 
 DS_OK = 0
+STATIC_SCRATCH_BYTES = 32 << 20   # DS_STATIC_SCRATCH_BYTES of include/ds.h
 STATUS_NAMES = {0: "DS_OK", 1: "DS_ERR_INVALID_ARG", 2: "DS_ERR_UNSUPPORTED", 3: "DS_ERR_WORKSPACE",
                 4: "DS_ERR_HIP", 5: "DS_ERR_BOUNDS"}
 KERNEL_CLASSES = ("layernorm", "gemm", "prefill_attn", "kv_migrate", "skinny_gemm", "decode_attn", "kv_append",
@@ -23,7 +24,8 @@ KERNEL_CLASSES = ("layernorm", "gemm", "prefill_attn", "kv_migrate", "skinny_gem
 
 # every symbol include/ds.h declares
 EXPORTS = ("ds_create", "ds_destroy", "ds_last_error", "ds_set_validate", "ds_prefill_workspace_bytes",
-           "ds_decode_workspace_bytes", "ds_prefill", "ds_kv_migrate", "ds_decode_step", "ds_layernorm",
+           "ds_decode_workspace_bytes", "ds_prefill", "ds_kv_migrate", "ds_decode_step", "ds_decode_step_static",
+           "ds_layernorm",
            "ds_linear_workspace_bytes", "ds_linear", "ds_prefill_attention", "ds_decode_attention",
            "ds_embed", "ds_next_token_workspace_bytes", "ds_next_token", "ds_profile_enable", "ds_profile_collect")
 
@@ -78,6 +80,9 @@ def load_library() -> ctypes.CDLL:
     lib.ds_decode_step.argtypes = [vp, ctypes.POINTER(LayerWeights), vp, vp, vp, i32, i32, i32, vp, vp, i32,
                                    vp, vp, sz, vp]
     lib.ds_decode_step.restype = ctypes.c_int
+    lib.ds_decode_step_static.argtypes = [vp, ctypes.POINTER(LayerWeights), vp, vp, vp, i32, i32, i32, vp, vp, i32,
+                                          vp, vp]
+    lib.ds_decode_step_static.restype = ctypes.c_int
     lib.ds_layernorm.argtypes = [vp, vp, vp, vp, i32, vp, vp]
     lib.ds_layernorm.restype = ctypes.c_int
     lib.ds_linear_workspace_bytes.argtypes = [vp, i32, i32, i32]
@@ -187,6 +192,12 @@ class Context:
                                             _ptr(block_tables), B, max_blocks_per_seq, max_ctx, _ptr(k_cache),
                                             _ptr(v_cache), num_blocks, _ptr(y), _ptr(workspace),
                                             _nbytes(workspace), _stream()))
+
+    def ds_decode_step_static(self, weights: LayerWeights, x, ctx_lens, block_tables, B: int,
+                              max_blocks_per_seq: int, max_ctx: int, k_cache, v_cache, num_blocks: int, y):
+        self._check(self.lib.ds_decode_step_static(self.handle, ctypes.byref(weights), _ptr(x), _ptr(ctx_lens),
+                                                   _ptr(block_tables), B, max_blocks_per_seq, max_ctx,
+                                                   _ptr(k_cache), _ptr(v_cache), num_blocks, _ptr(y), _stream()))
 
     # ---- single steps ----
     def ds_layernorm(self, x, gamma, beta, rows: int, out):

@@ -33,7 +33,7 @@ struct ds_ctx {
   mutable std::map<std::pair<int, int>, size_t> decode_ws;
 };
 
-// ---- per-device set-up: kernel attributes ----
+// ---- per-device set-up: kernel attributes, address of the static scratch array ----
 namespace ds {
 namespace {
 std::vector<std::pair<const void*, int>>& attr_list() {
@@ -51,17 +51,25 @@ hipError_t configure_kernels() {
 }
 }  // namespace ds
 
+// Scratch of ds_decode_step_static: the decode step's workspace (activations between its kernels, split-K
+// and attention partials) for callers that cannot bring one.  One copy per GPU the library runs on, held
+// until the process ends.  In host code this name is only a handle for hipGetSymbolAddress: kernels and
+// copies are given the per-device address kept in DeviceState::scratch, never the name.
+static __device__ __align__(256) unsigned char scratch[DS_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int kMaxDevices = 64;
 struct DeviceState {
   bool ready = false;
+  void* scratch = nullptr;  // this device's address of `scratch`
 };
 std::mutex g_dev_mu;
 DeviceState g_dev[kMaxDevices];
 
-// Once per device, with that device current: function attributes of every kernel.  Returns the device's
-// state, or null with *err set.
+// Once per device, with that device current: function attributes of every kernel, and the device address
+// of `scratch` (each GPU holds its own copy of the array at its own address).  Returns the device's state,
+// or null with *err set.
 const DeviceState* device_state(hipError_t* err) {
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
@@ -74,10 +82,13 @@ const DeviceState* device_state(hipError_t* err) {
   DeviceState& st = g_dev[dev];
   if (!st.ready) {
     e = ds::configure_kernels();
-    if (e != hipSuccess) {
-      *err = e;
+    void* ptr = nullptr;
+    if (e == hipSuccess) e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      *err = e != hipSuccess ? e : hipErrorInvalidSymbol;
       return nullptr;
     }
+    st.scratch = ptr;
     st.ready = true;
   }
   *err = hipSuccess;
@@ -320,7 +331,7 @@ ds_status ds_create(const ds_model_cfg* cfg, ds_ctx** out) {
   c->profile = false;
   const char* dbg = getenv("DS_DEBUG_VALIDATE");
   c->validate = dbg && dbg[0] && strcmp(dbg, "0") != 0;
-  // One-time set-up of the current device (kernel attributes).  Without a usable device
+  // One-time set-up of the current device (kernel attributes, scratch address).  Without a usable device
   // the context is still good for the size queries; the first call that launches reports the failure.
   hipError_t e;
   (void)device_state(&e);
@@ -640,10 +651,12 @@ ds_status ds_decode_attention(ds_ctx* ctx, const void* q, const int32_t* kv_lens
   return DS_OK;
 }
 
-ds_status ds_decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, const int32_t* ctx_lens,
-                         const int32_t* block_tables, int32_t B, int32_t max_blocks_per_seq, int32_t max_ctx,
-                         void* k_cache, void* v_cache, int32_t num_blocks, void* y, void* workspace,
-                         size_t workspace_bytes, void* stream) {
+// Both decode-step entry points: `workspace` is the caller's buffer, or null for the static scratch array
+// of the current device (then the step must fit DS_STATIC_SCRATCH_BYTES).
+static ds_status decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, const int32_t* ctx_lens,
+                             const int32_t* block_tables, int32_t B, int32_t max_blocks_per_seq, int32_t max_ctx,
+                             void* k_cache, void* v_cache, int32_t num_blocks, void* y, void* workspace,
+                             size_t workspace_bytes, bool use_static, void* stream) {
   if (!ctx) return DS_ERR_INVALID_ARG;
   ds_status st = check_weights(ctx, w);
   if (st != DS_OK) return st;
@@ -658,9 +671,20 @@ ds_status ds_decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, 
   if (!aligned16(x) || !aligned16(y) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(workspace))
     return fail(ctx, DS_ERR_INVALID_ARG, "ds_decode_step: pointers must be 16-byte aligned");
   const size_t need = ds_decode_workspace_bytes(ctx, B, max_ctx);
-  if (!workspace || workspace_bytes < need)
-    return fail(ctx, DS_ERR_WORKSPACE, "ds_decode_step: workspace %zu < %zu", workspace_bytes, need);
-  if ((st = ensure_device(ctx)) != DS_OK) return st;
+  const DeviceState* dev = nullptr;
+  if (use_static) {
+    if (need > (size_t)DS_STATIC_SCRATCH_BYTES)
+      return fail(ctx, DS_ERR_WORKSPACE,
+                  "ds_decode_step_static: this step needs %zu bytes of scratch, the static array holds %zu "
+                  "(use ds_decode_step with a workspace)", need, (size_t)DS_STATIC_SCRATCH_BYTES);
+    if ((st = ensure_device(ctx, &dev)) != DS_OK) return st;
+    workspace = dev->scratch;
+    workspace_bytes = (size_t)DS_STATIC_SCRATCH_BYTES;
+  } else {
+    if (!workspace || workspace_bytes < need)
+      return fail(ctx, DS_ERR_WORKSPACE, "ds_decode_step: workspace %zu < %zu", workspace_bytes, need);
+    if ((st = ensure_device(ctx)) != DS_OK) return st;
+  }
 
   const ds_model_cfg& c = ctx->cfg;
   const int h = c.hidden, m = c.ffn;
@@ -734,6 +758,22 @@ ds_status ds_decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, 
     if (st != DS_OK) return st;
   }
   return DS_OK;
+}
+
+ds_status ds_decode_step(ds_ctx* ctx, const ds_layer_weights* w, const void* x, const int32_t* ctx_lens,
+                         const int32_t* block_tables, int32_t B, int32_t max_blocks_per_seq, int32_t max_ctx,
+                         void* k_cache, void* v_cache, int32_t num_blocks, void* y, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  return decode_step(ctx, w, x, ctx_lens, block_tables, B, max_blocks_per_seq, max_ctx, k_cache, v_cache,
+                     num_blocks, y, workspace, workspace_bytes, false, stream);
+}
+
+ds_status ds_decode_step_static(ds_ctx* ctx, const ds_layer_weights* w, const void* x, const int32_t* ctx_lens,
+                                const int32_t* block_tables, int32_t B, int32_t max_blocks_per_seq,
+                                int32_t max_ctx, void* k_cache, void* v_cache, int32_t num_blocks, void* y,
+                                void* stream) {
+  return decode_step(ctx, w, x, ctx_lens, block_tables, B, max_blocks_per_seq, max_ctx, k_cache, v_cache,
+                     num_blocks, y, nullptr, 0, true, stream);
 }
 
 ds_status ds_profile_enable(ds_ctx* ctx, int32_t on) {
