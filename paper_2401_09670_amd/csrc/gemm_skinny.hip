@@ -34,6 +34,10 @@
 
 namespace ds {
 
+// Cache policy operand of the direct-to-LDS weight loads: 2 = non-temporal.  A weight byte is used once per
+// launch, so it is not worth a line in L2 or the last-level cache (measured: 42.4 -> 41.3 us per decode GEMM
+// at OPT-13B, batch 64); the activation slabs, re-read by every workgroup, keep the default policy.
+constexpr int kWeightAux = 2;
 constexpr int kSkThreads = 512;
 constexpr int kSkWaves = kSkThreads / 64;
 constexpr int kSkKS = 128;  // k elements per slab
@@ -113,10 +117,16 @@ __global__ __launch_bounds__(kSkThreads) void skinny_gemm_kernel(const SkinnyPar
     const int ofs = min(i, ns - 1) * n_splits * kSkKS;
     uint16_t* dst = lds + st * STAGE_ELEMS + wave_s * 512;  // one wave-load = 4 rows = 1 KB = 512 elements
 #pragma unroll
-    for (int j = 0; j < G; ++j)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ofs),
-                                       (__attribute__((address_space(3))) void*)(dst + j * kSkWaves * 512), 16,
-                                       0, 0);
+    for (int j = 0; j < G; ++j) {
+      if (j < MP / (4 * kSkWaves))  // activation rows
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ofs),
+                                         (__attribute__((address_space(3))) void*)(dst + j * kSkWaves * 512), 16,
+                                         0, 0);
+      else
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ofs),
+                                         (__attribute__((address_space(3))) void*)(dst + j * kSkWaves * 512), 16,
+                                         0, kWeightAux);
+    }
   };
 
   floatx4 acc[NTW][MT];
@@ -326,9 +336,14 @@ __global__ __launch_bounds__(64 * NW) void wring_gemm_kernel(const SkinnyParams 
     const int ofs = min(i, ns - 1) * NW * kWrKS;
     uint16_t* dst = ring + st * kWrStageElems;
 #pragma unroll
-    for (int j = 0; j < kWrLoads; ++j)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ofs),
-                                       (__attribute__((address_space(3))) void*)(dst + j * 512), 16, 0, 0);
+    for (int j = 0; j < kWrLoads; ++j) {
+      if (j < kWrBM / 8)  // activation rows
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ofs),
+                                         (__attribute__((address_space(3))) void*)(dst + j * 512), 16, 0, 0);
+      else
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ofs),
+                                         (__attribute__((address_space(3))) void*)(dst + j * 512), 16, 0, kWeightAux);
+    }
   };
 
   floatx4 acc[NT][MT];  // [weight row tile a][activation row tile t]
