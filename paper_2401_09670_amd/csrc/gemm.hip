@@ -18,7 +18,14 @@
 namespace ds {
 
 constexpr int kBK = 64;
-constexpr int kGemmThreads = 256;
+
+// LDS a workgroup asks for: its ring of operand stages - or the whole 160 KB of the compute unit once the ring
+// alone is more than half of it (a second workgroup could not move in anyway), which gives the epilogue a
+// larger staging area: more columns per pass, longer contiguous row pieces in the output stores.
+constexpr int gemm_lds_bytes(int BM, int BN, int STAGES) {
+  const int ring = STAGES * (BM + BN) * kBK * 2;
+  return ring > 80 * 1024 ? 160 * 1024 : ring;
+}
 
 struct GemmParams {
   const uint16_t* X;
@@ -45,7 +52,20 @@ struct GemmParams {
   uint16_t* k_cache;
   uint16_t* v_cache;
   int n_heads, n_kv_heads, head_dim;
+#ifdef DS_DEV_SWITCHES
+  unsigned long long* dbg;  // timing harness builds only: 4 wall-clock stamps per workgroup
+#endif
 };
+
+#ifdef DS_DEV_SWITCHES
+unsigned long long* g_gemm_dbg = nullptr;
+#define DS_STAMP(i)                                                                         \
+  do {                                                                                      \
+    if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)(blockIdx.x + gridDim.x * blockIdx.y) * 4 + (i)] = __builtin_amdgcn_s_memrealtime(); \
+  } while (0)
+#else
+#define DS_STAMP(i)
+#endif
 
 // Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs (each with a private L2).  With one
 // contiguous m-fastest range of tiles per XCD and many row tiles (long prefill batches), the 32 workgroups an
@@ -96,16 +116,19 @@ __device__ __forceinline__ void wait_vmcnt() {
 enum { kEpiPlain = 0, kEpiPartial = 1, kEpiKvScatter = 2 };
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int EPI>
-__global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams p) {
-  static_assert(WAVES_M * WAVES_N == 4, "4 waves");
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_dl_kernel(const GemmParams p) {
+  // One wave per SIMD.  (Eight waves - two per SIMD, 128 accumulator registers each - were measured on the
+  // 256x256 tile: equal as 4x2 waves of 64x128, 7 % slower as 2x4 of 128x64; the loop is not latency-bound.)
+  constexpr int NW = WAVES_M * WAVES_N;
+  static_assert(NW == 4, "4 waves");
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
-  static_assert(BM % 32 == 0 && BN % 32 == 0, "a wave-level load covers 8 rows; 4 waves");
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "a wave-level load covers 8 rows");
   constexpr int ROW_BYTES = kBK * 2;                      // 128
   constexpr int STAGE_ELEMS = (BM + BN) * kBK;            // elements per stage
-  constexpr int XL = BM / 32;                             // X loads per wave per stage
-  constexpr int WL = BN / 32;                             // W loads per wave per stage
+  constexpr int XL = BM / (8 * NW);                       // X loads per wave per stage
+  constexpr int WL = BN / (8 * NW);                       // W loads per wave per stage
   constexpr int LPS = XL + WL;
   static_assert((STAGES - 1) * LPS < 64, "vmcnt range");
 
@@ -116,6 +139,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   const int wave = tid >> 6;
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
 
+  DS_STAMP(0);
   int tile_m, tile_n;
   patch_tile(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
   const int m0 = tile_m * BM;
@@ -129,21 +153,21 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   const int KT = (K / kBK - kt_first + kt_step - 1) / kt_step;  // >= 1: splits <= K / 64
 
   // per-lane source offsets (bytes, from the tile's first row) of this wave's loads; load j covers rows
-  // 8*(4j+wave) .. +7.  With the tile origin and the k position in a scalar base, the lane part is a 32-bit
+  // 8*(NW*j+wave) .. +7.  With the tile origin and the k position in a scalar base, the lane part is a 32-bit
   // value that never changes, and a load needs no vector arithmetic at all.
   const int lrow = lane >> 3;
-  const int lchunk = (lane & 7) ^ (4 * (wave & 1) + (lane >> 4));  // key = (row >> 1) & 7, row = 8*(4j+wave) + lane/8
+  const int lchunk = (lane & 7) ^ (4 * (wave & 1) + (lane >> 4));  // key = (row >> 1) & 7, row = 8*(NW*j+wave) + lane/8
   const char* xbase = reinterpret_cast<const char*>(p.X + (size_t)m0 * p.ldx);
   const char* wbase = reinterpret_cast<const char*>(p.W + (size_t)n0 * K);
   uint32_t xoff[XL], woff[WL];
 #pragma unroll
   for (int j = 0; j < XL; ++j) {
-    const int row = min(8 * (4 * j + wave) + lrow, p.M - 1 - m0);
+    const int row = min(8 * (NW * j + wave) + lrow, p.M - 1 - m0);
     xoff[j] = ((uint32_t)row * (uint32_t)p.ldx + lchunk * 8) * 2u;
   }
 #pragma unroll
   for (int j = 0; j < WL; ++j) {
-    const int row = min(8 * (4 * j + wave) + lrow, p.N - 1 - n0);
+    const int row = min(8 * (NW * j + wave) + lrow, p.N - 1 - n0);
     woff[j] = ((uint32_t)row * (uint32_t)K + lchunk * 8) * 2u;
   }
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);  // keep LDS destinations in scalar registers
@@ -159,11 +183,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
     asm volatile("" : "+v"(off));
     if (j < XL) {
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xbase + kofs + off),
-                                       (__attribute__((address_space(3))) void*)(xb + j * 2048), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(xb + j * NW * 512), 16, 0, 0);
     } else {
       __builtin_amdgcn_global_load_lds(
           (const __attribute__((address_space(1))) void*)(wbase + kofs + off),
-          (__attribute__((address_space(3))) void*)(xb + BM * kBK + (j - XL) * 2048), 16, 0, 0);
+          (__attribute__((address_space(3))) void*)(xb + BM * kBK + (j - XL) * NW * 512), 16, 0, 0);
     }
   };
   auto issue = [&](int stage, int kt_load) {
@@ -243,8 +267,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   // Each wave stages its own WTM x (GA*32) fp32 block (GA column tiles per pass) in LDS that the
   // k-loop no longer needs; rows are padded by 4 floats so the 16-byte transposing writes of 16
   // lanes fall into distinct banks.
-  constexpr int LDS_FLOATS = STAGES * STAGE_ELEMS / 2;
-  constexpr int GA_FIT = (LDS_FLOATS / (4 * WTM) - 4) / 32;
+  constexpr int LDS_FLOATS = gemm_lds_bytes(BM, BN, STAGES) / 4;
+  constexpr int GA_FIT = (LDS_FLOATS / (NW * WTM) - 4) / 32;
   constexpr int GA = GA_FIT < TN ? GA_FIT : TN;
   static_assert(GA >= 1, "no room to stage the epilogue");
   constexpr int RSTR = GA * 32 + 4;  // staging row stride in floats
@@ -291,6 +315,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
     for (int st = 0; st < STAGES; ++st) issue(st, st);
     wait_vmcnt<(STAGES - 1) * LPS>();
     __syncthreads();
+    DS_STAMP(1);
 #pragma unroll
     for (int r = 0; r < NR; ++r) frag_read(fa, lds, 0, r);
 
@@ -330,6 +355,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
   // k-loop no longer needs; rows are padded by 4 floats so the 16-byte transposing writes of 16
   // lanes fall into distinct banks.
   __syncthreads();                 // every wave has finished reading the k-loop buffers
+  DS_STAMP(2);
   float* stg = reinterpret_cast<float*>(lds) + wave * (WTM * RSTR);
 #pragma unroll
   for (int pass = 0; pass < NPASS; ++pass) {
@@ -405,17 +431,18 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_dl_kernel(const GemmParams 
       }
     }
   }
+  DS_STAMP(3);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int EPI>
 static hipError_t launch_dl_epi(GemmParams p, int splits, hipStream_t stream) {
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N - p.n_base + BN - 1) / BN;
-  constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * kBK * sizeof(uint16_t);
-  static_assert(lds_bytes <= 160 * 1024, "LDS");
+  constexpr size_t lds_bytes = gemm_lds_bytes(BM, BN, STAGES);
+  static_assert((size_t)STAGES * (BM + BN) * kBK * sizeof(uint16_t) <= lds_bytes && lds_bytes <= 160 * 1024, "LDS");
   constexpr auto kern = gemm_dl_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, EPI>;
   (void)KernelAttrReg<kern, (int)lds_bytes>::done;
-  hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n, splits), dim3(kGemmThreads), lds_bytes, stream, p);
+  hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n, splits), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
@@ -588,6 +615,9 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
   p.partial = nullptr;
   p.ctx_lens = nullptr; p.block_tables = nullptr; p.max_blocks = 0;
   p.k_cache = nullptr; p.v_cache = nullptr; p.n_heads = 0; p.n_kv_heads = 0; p.head_dim = 0;
+#ifdef DS_DEV_SWITCHES
+  p.dbg = g_gemm_dbg;
+#endif
   GemmPlan pl = gemm_plan(M, N, K);
   if (pl.splits > 1 && workspace == nullptr) pl.splits = 1;  // no room for partials: slower, still right
   if (pl.splits > 1 && ep.out_ld != 0) return hipErrorInvalidValue;  // the reduce pass writes dense rows
