@@ -126,13 +126,18 @@ def main():
     # ---------------- warm-up, then the timed region ----------------
     for _ in range(args.warmup):
         one_step()
+    step_marks = [ev() for _ in range(args.steps + 1)]   # events between the steps: recording one does not wait
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    step_marks[0].record()
+    for i in range(args.steps):
         one_step()
+        step_marks[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+    per_step = sorted(step_marks[i].elapsed_time(step_marks[i + 1]) for i in range(args.steps))
+    ms_median, ms_min = per_step[len(per_step) // 2], per_step[0]
     tokens_per_step = B_dec * ctx0 + B_dec * steps_dec
     value = tokens_per_step / (ms_per_step * 1e-3)
 
@@ -175,14 +180,23 @@ def main():
     }
     # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (separate runs of this same
     # command, scaled by a known-size copy); the summary and its commands are kept under profiles/.
-    traffic = {}
+    # These are stored figures, not measured in this run: they carry the hash of the kernel sources they were
+    # measured on, and are dropped (traffic = null, traffic_source.stale = true) when the sources have changed.
+    traffic, traffic_source = {}, None
     tpath = os.path.join(ROOT, "profiles", "bench_opt13b_1layer_hbm_traffic.json")
     if not args.small and os.path.exists(tpath):
+        from paper_2401_09670_amd import profile_summary
         with open(tpath) as f:
-            per = json.load(f)["per_launch"]
-        traffic = {k: v["hbm_read_bytes"] + v["hbm_write_bytes"] for k, v in per.items()}
-        if "decode_gemm_call" in per:   # the class timed as skinny_gemm = either streaming kernel + its reduce launch
-            traffic["skinny_gemm"] = per["decode_gemm_call"]["hbm_read_bytes"] + per["decode_gemm_call"]["hbm_write_bytes"]
+            stored = json.load(f)
+        stale = stored.get("source_stamp") != profile_summary.source_stamp()
+        traffic_source = {"file": "profiles/bench_opt13b_1layer_hbm_traffic.json",
+                          "measured_on_sources": stored.get("source_stamp"), "stale": stale}
+        if not stale:
+            per = stored["per_launch"]
+            traffic = {k: v["hbm_read_bytes"] + v["hbm_write_bytes"] for k, v in per.items()}
+            if "decode_gemm_call" in per:   # the class timed as skinny_gemm = either streaming kernel + its reduce launch
+                traffic["skinny_gemm"] = (per["decode_gemm_call"]["hbm_read_bytes"]
+                                          + per["decode_gemm_call"]["hbm_write_bytes"])
     kernels = {}
     for name, (bound, amount, peak) in work.items():
         ms, cnt = prof[name]
@@ -200,6 +214,8 @@ def main():
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     roofline = dict(kernels[dominant])
     roofline["kernel"] = dominant
+    roofline["traffic_source"] = traffic_source
+    roofline["timed_in"] = "a separate pass of the same steps with HIP events around every launch"
 
     # ---------------- phase metrics ----------------
     prefill_tok_s = n_prefill * t / (phase["prefill_ms"] * 1e-3)
@@ -332,6 +348,7 @@ def main():
         "value": round(value, 1),
         "unit": "tokens/s (prompt+generated, one OPT-13B layer: 16x prefill(4x512)+migrate, 64x decode(B=64))",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(ms_median, 4), "ms_per_step_min": round(ms_min, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg["name"], "hidden": h, "heads": n, "head_dim": s, "ffn": m, "layers": 1,
                    "prefill_batches_per_step": n_prefill, "prefill_lens": lens, "decode_batch": B_dec,
@@ -340,6 +357,9 @@ def main():
         "phases": phases,
         "roofline": roofline,
         "kernels": kernels,
+        "kernels_timed_in": "a separate pass of the same steps with HIP events around every launch (event overhead "
+                            "included, so the classes sum to slightly more than ms_per_step); phases: a third pass with "
+                            "events at the phase boundaries only",
         "extras": extras,
         "cpu_baseline": cpu_baseline,
         "setup_s": round(setup_s, 1),

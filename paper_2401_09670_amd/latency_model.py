@@ -138,7 +138,9 @@ class _Layer:
         return lambda: self.ctx.ds_decode_step(self.lw, x, lens, bt_d, B, mb, ctx_len + 1, kc, vc, nblk, y, ws)
 
 
-def run_sweeps(model: str, quick: bool, log=lambda s: None) -> dict:
+def run_sweeps(model: str, quick: bool, log=lambda s: None, interference_lens=None) -> dict:
+    """All three sweeps on one layer of `model`.  `interference_lens` overrides the prompt lengths of the
+    interference measurement (default: 128 in quick mode, 128 and 1024 otherwise)."""
     import torch
     from . import synth
     shape = {"opt13b": synth.OPT_13B, "opt66b": synth.OPT_66B, "opt175b": synth.OPT_175B, "tiny": synth.TINY}[model]
@@ -201,7 +203,7 @@ def run_sweeps(model: str, quick: bool, log=lambda s: None) -> dict:
     # ---- interference (Sec. 2.3): a decoding-only step versus the same step with one prefill added,
     #      serialised on the one GPU (this library never mixes the phases inside a kernel) ----
     inter = []
-    for l_in in ([128] if quick else [128, 1024]):
+    for l_in in (interference_lens if interference_lens is not None else ([128] if quick else [128, 1024])):
         pf = layer.prefill_fn([l_in])
         ms_pre = _time_ms(pf, torch, reps)
         for B in ([1, 64] if quick else [1, 4, 16, 64, 128]):

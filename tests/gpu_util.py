@@ -34,6 +34,14 @@ def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
     return float(np.max(np.abs(gpu - ref)) / np.max(np.abs(ref)))
 
 
+def rel_err_rows(gpu: np.ndarray, ref: np.ndarray) -> float:
+    """The same metric taken row by row (rows = first axis) and maximised: a row of small magnitude that is
+    entirely wrong cannot hide behind a large row elsewhere in the tensor."""
+    g = gpu.reshape(gpu.shape[0], -1)
+    r = ref.reshape(ref.shape[0], -1)
+    return float(np.max(np.max(np.abs(g - r), axis=1) / np.max(np.abs(r), axis=1)))
+
+
 def make_ctx(shape) -> binding.Context:
     return binding.Context(shape.hidden, shape.n_heads, shape.head_dim, shape.ffn, shape.block_size, shape.ln_eps,
                            shape.n_kv_heads)

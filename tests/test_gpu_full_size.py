@@ -37,19 +37,30 @@ def test_prefill_full_size_sampled_rows(cfg2):
     ctx.ds_prefill(cfg2["lw"], gu.to_dev(xbits), gu.i32_dev(synth.cu_seqlens(lens)), len(lens), t, max(lens), y,
                    k_out, v_out, ws)
     torch.cuda.synchronize()
-    seq = 2
-    r0 = sum(lens[:seq])
-    rows = [0, 1, 127, 128, 255, 300, 510, 511]
-    yr, kr, vr = orc.layer_prefill_rows(cfg2["w64"], orc.from_bf16_bits(xbits[r0:r0 + lens[seq]]), rows,
-                                        shape.n_heads, shape.ln_eps)
-    yg = gu.to_f64(y)[r0:r0 + lens[seq]]
-    assert gu.rel_err(yg[rows], yr) < TOL
-    # the layer's own contribution (output minus the residual input) is checked too: the residual
-    # stream dominates y, so this is the sharper test of attention + FFN
-    xin = orc.from_bf16_bits(xbits[r0:r0 + lens[seq]])[rows]
-    assert gu.update_ok(yg[rows], yr, xin)
-    assert gu.rel_err(gu.to_f64(k_out)[r0:r0 + lens[seq]], kr.reshape(lens[seq], h)) < TOL
-    assert gu.rel_err(gu.to_f64(v_out)[r0:r0 + lens[seq]], vr.reshape(lens[seq], h)) < TOL
+    # 32 rows of every prompt: both ends, both sides of every 128-row tile edge of the attention kernel, and a
+    # seeded draw of the rest; the prompt's K and V are compared in full
+    rng = np.random.Generator(np.random.Philox(key=[seed, 77]))
+    yg_all, kg_all, vg_all = gu.to_f64(y), gu.to_f64(k_out), gu.to_f64(v_out)
+    for seq in range(len(lens)):
+        r0, l = sum(lens[:seq]), lens[seq]
+        fixed = [0, 1, 63, 64, 127, 128, 255, 256, 383, 384, l - 2, l - 1]
+        extra = [int(r) for r in rng.permutation(l) if int(r) not in fixed][:32 - len(fixed)]
+        rows = sorted(fixed + extra)
+        assert len(rows) == 32
+        yr, kr, vr = orc.layer_prefill_rows(cfg2["w64"], orc.from_bf16_bits(xbits[r0:r0 + l]), rows,
+                                            shape.n_heads, shape.ln_eps)
+        yg = yg_all[r0:r0 + l]
+        assert gu.rel_err(yg[rows], yr) < TOL, seq
+        assert gu.rel_err_rows(yg[rows], yr) < TOL, seq
+        # the layer's own contribution (output minus the residual input) is checked too: the residual
+        # stream dominates y, so this is the sharper test of attention + FFN
+        xin = orc.from_bf16_bits(xbits[r0:r0 + l])[rows]
+        assert gu.update_ok(yg[rows], yr, xin), seq
+        assert gu.rel_err(kg_all[r0:r0 + l], kr.reshape(l, h)) < TOL, seq
+        assert gu.rel_err(vg_all[r0:r0 + l], vr.reshape(l, h)) < TOL, seq
+        # per (token, head) rows of K and V as well: one wrong head must not hide in the tensor's maximum
+        assert gu.rel_err_rows(kg_all[r0:r0 + l].reshape(l * shape.n_heads, -1), kr.reshape(l * shape.n_heads, -1)) < 2 * TOL
+        assert gu.rel_err_rows(vg_all[r0:r0 + l].reshape(l * shape.n_heads, -1), vr.reshape(l * shape.n_heads, -1)) < 2 * TOL
 
 
 def test_migrate_full_size_bit_exact(cfg2):
@@ -92,7 +103,7 @@ def test_decode_full_size_sampled_sequences(cfg2):
         ys.append(gu.to_f64(y))
     torch.cuda.synchronize()
 
-    sample = [0, 31, 63]
+    sample = [0, 9, 18, 27, 31, 40, 54, 63]     # 8 of the 64 sequences, all 8 distinct cache contents
     sbt, snblk = synth.make_block_tables([ctx0 + steps] * len(sample), 16, seed + 1)
     okc = np.zeros((snblk, n, 16, s))
     ovc = np.zeros_like(okc)
@@ -102,6 +113,7 @@ def test_decode_full_size_sampled_sequences(cfg2):
         xin = orc.from_bf16_bits(xs[j][sample])
         yr = orc.layer_decode_cached(cfg2["w64"], xin, [ctx0 + j] * len(sample), sbt, okc, ovc, n, shape.ln_eps)
         assert gu.rel_err(ys[j][sample], yr) < TOL, j
+        assert gu.rel_err_rows(ys[j][sample], yr) < TOL, j
         assert gu.update_ok(ys[j][sample], yr, xin), j
     # the appended K,V rows of the sampled sequences
     got_k = gu.to_bits(kc_d)
