@@ -188,6 +188,15 @@ ds_status ds_layernorm(ds_ctx *ctx, const void *x, const void *gamma, const void
  * ds_linear_workspace_bytes(rows, ...) bytes for fp32 partial sums (0 = none
  * needed for this shape). */
 size_t ds_linear_workspace_bytes(const ds_ctx *ctx, int32_t rows, int32_t in_f, int32_t out_f);
+/* Which kernel a ds_linear call of this shape takes (host-side planning only, nothing is launched):
+ * *streaming = 1 for the weight-streaming kernels of the decode phase (then tile_rows = tile_cols = 0),
+ * 0 for the MFMA tile kernel with tiles of tile_rows x tile_cols outputs; *splits = workgroups the
+ * reduction dimension is split over (1 = not split; a split launch is followed by a reduce pass);
+ * *cut_cols > 0 = the output columns from there on run as a second launch on a smaller tile.
+ * App. A.2 / A.3 give the product shapes; the plan is this library's answer to how many tokens it takes
+ * to fill the chip (Sec. 3.1). */
+ds_status ds_linear_plan(const ds_ctx *ctx, int32_t rows, int32_t in_f, int32_t out_f, int32_t *streaming,
+                         int32_t *tile_rows, int32_t *tile_cols, int32_t *splits, int32_t *cut_cols);
 ds_status ds_linear(ds_ctx *ctx, const void *x, const void *w, const void *bias,
                     const void *residual, int32_t relu, int32_t rows, int32_t in_f, int32_t out_f,
                     void *y, void *workspace, size_t workspace_bytes, void *stream);

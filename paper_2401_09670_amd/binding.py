@@ -26,7 +26,7 @@ KERNEL_CLASSES = ("layernorm", "gemm", "prefill_attn", "kv_migrate", "skinny_gem
 EXPORTS = ("ds_create", "ds_destroy", "ds_last_error", "ds_set_validate", "ds_prefill_workspace_bytes",
            "ds_decode_workspace_bytes", "ds_prefill", "ds_kv_migrate", "ds_decode_step", "ds_decode_step_static",
            "ds_layernorm",
-           "ds_linear_workspace_bytes", "ds_linear", "ds_prefill_attention", "ds_decode_attention",
+           "ds_linear_workspace_bytes", "ds_linear_plan", "ds_linear", "ds_prefill_attention", "ds_decode_attention",
            "ds_embed", "ds_next_token_workspace_bytes", "ds_next_token", "ds_profile_enable", "ds_profile_collect")
 
 
@@ -87,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     lib.ds_layernorm.restype = ctypes.c_int
     lib.ds_linear_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.ds_linear_workspace_bytes.restype = sz
+    lib.ds_linear_plan.argtypes = [vp, i32, i32, i32] + [ctypes.POINTER(ctypes.c_int32)] * 5
+    lib.ds_linear_plan.restype = ctypes.c_int
     lib.ds_linear.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
     lib.ds_linear.restype = ctypes.c_int
     lib.ds_prefill_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp]
@@ -203,6 +205,12 @@ class Context:
     def ds_layernorm(self, x, gamma, beta, rows: int, out):
         self._check(self.lib.ds_layernorm(self.handle, _ptr(x), _ptr(gamma), _ptr(beta), rows, _ptr(out),
                                           _stream()))
+
+    def ds_linear_plan(self, rows: int, in_f: int, out_f: int) -> dict:
+        v = [ctypes.c_int32() for _ in range(5)]
+        self._check(self.lib.ds_linear_plan(self.handle, rows, in_f, out_f, *[ctypes.byref(a) for a in v]))
+        return dict(streaming=bool(v[0].value), tile_rows=v[1].value, tile_cols=v[2].value, splits=v[3].value,
+                    cut_cols=v[4].value)
 
     def ds_linear(self, x, w, bias, residual, relu: int, rows: int, in_f: int, out_f: int, y, workspace=None):
         self._check(self.lib.ds_linear(self.handle, _ptr(x), _ptr(w), _ptr(bias), _ptr(residual), relu, rows,

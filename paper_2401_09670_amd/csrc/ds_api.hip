@@ -412,6 +412,25 @@ size_t ds_linear_workspace_bytes(const ds_ctx* ctx, int32_t rows, int32_t in_f, 
   return in_f % 64 == 0 ? linear_ws_exact(rows, in_f, out_f) : 0;
 }
 
+ds_status ds_linear_plan(const ds_ctx* ctx, int32_t rows, int32_t in_f, int32_t out_f, int32_t* streaming,
+                         int32_t* tile_rows, int32_t* tile_cols, int32_t* splits, int32_t* cut_cols) {
+  if (!ctx || !streaming || !tile_rows || !tile_cols || !splits || !cut_cols || rows <= 0 || in_f <= 0 ||
+      out_f <= 0 || in_f % 64 != 0)
+    return DS_ERR_INVALID_ARG;
+  *streaming = use_skinny(rows, in_f) ? 1 : 0;
+  *tile_rows = *tile_cols = *cut_cols = 0;
+  *splits = 1;
+  if (*streaming) {
+    const size_t ws = ds::skinny_workspace_bytes(rows, out_f, in_f);
+    *splits = ws ? (int32_t)(ws / ((size_t)rows * out_f * sizeof(float))) : 1;
+  } else {
+    int tr, tc, sp, cut;
+    ds::gemm_describe(rows, out_f, in_f, &tr, &tc, &sp, &cut);
+    *tile_rows = tr; *tile_cols = tc; *splits = sp; *cut_cols = cut;
+  }
+  return DS_OK;
+}
+
 ds_status ds_linear(ds_ctx* ctx, const void* x, const void* w, const void* bias, const void* residual,
                     int32_t relu, int32_t rows, int32_t in_f, int32_t out_f, void* y, void* workspace,
                     size_t workspace_bytes, void* stream) {

@@ -466,12 +466,15 @@ static double tile_cost(int M, int N, int BM, int BN, double factor) {
   return rounds * BM * BN * factor;
 }
 
-DS_SWITCH(g_gemm_variant, 0);  // 0 = cost model, 1..4 force a tile
-DS_SWITCH(g_gemm_splits, 0);   // 0 = plan, > 0 force the split count
+DS_SWITCH(g_gemm_variant, 0);     // 0 = cost model, 1..5 force a tile
+DS_SWITCH(g_gemm_splits, 0);      // 0 = plan, > 0 force the split count
+DS_SWITCH(g_gemm_tail_split, 1);  // 0 = never cut a product at a column
 
 struct GemmPlan {
-  int variant;  // 1: 256x160, 2: 128x128, 3: 256x256, 4: 64x128
+  int variant;  // 1: 256x160, 2: 128x128, 3: 256x256, 4: 64x128, 5: 128x256
   int splits;
+  int cut_cols = 0;     // > 0: the product is cut at this column; [0, cut_cols) on `variant`, the rest on ...
+  int tail_variant = 0; // ... this tile, as a second launch
 };
 
 // Tile shape by the cost model above; split count so that a launch with few tiles still occupies the
@@ -507,8 +510,77 @@ static GemmPlan decode_plan(int M, int N, int K) {
   return best;
 }
 
+// Prefill-sized products (more than 256 rows): tile shape, split count and column cut together, by a time
+// model fitted to this chip (OPT-13B shapes, 512-2048 rows, weights not resident in any cache).
+//  * A workgroup's k-loop costs us_per_kk microseconds per 1000 elements of K when all 256 compute units are
+//    busy, plus t0 for its prologue and epilogue (the output burst of a whole round of tiles is bound by write
+//    bandwidth: 9 us for 256x256 tiles, 5 us for 256x160).
+//  * Fewer workgroups than compute units: the busy ones clock higher (the chip is power-limited under matrix
+//    load), so only 30 % of the idle share is charged.  A partly filled round after full ones is charged
+//    80 % of its idle share: its tiles cost what the full rounds' tiles cost.
+//  * Splitting K pays where the tiles alone leave most of the chip idle - 512 to 1024 rows against 5120
+//    output columns: FFN-out of OPT-13B at 512 rows 186 -> 118 us on four splits of 256x160 tiles, at 1024
+//    rows 357 -> 202 us on two.  It costs the fp32 partials' round trip (cheap while they fit the caches) and
+//    a reduce launch, and is only considered for launches that stay within one round.
+//  * Tile quantisation: 2.5 rounds cost nearly 3.  A product may be cut at a column: the leading columns keep
+//    the large tile in whole rounds, the rest runs as a second launch on 256x160 or 128x128 tiles (bias,
+//    residual and output pointers follow the cut).  FFN-in of OPT-13B at 2048 rows: 383 us whole, 348 us as
+//    two rounds of 256x256 tiles plus one of 256x160.
+struct TileModel {
+  int variant, bm, bn;
+  double us_per_kk, t0;
+};
+static const TileModel kTileModels[] = {{3, 256, 256, 24.2, 11.6}, {1, 256, 160, 16.5, 7.9},
+                                        {5, 128, 256, 15.0, 8.0}, {2, 128, 128, 11.5, 6.0}};
+// time of `tiles` workgroups of tile t over K (one launch, no split)
+static double tiles_us(const TileModel& t, long tiles, double K) {
+  const double exact = tiles / 256.0, full = (double)((tiles + 255) / 256);
+  if (tiles <= 256) return (0.7 + 0.3 * exact) * t.us_per_kk * K * 1e-3 + t.t0;
+  return (exact + 0.8 * (full - exact)) * (t.us_per_kk * K * 1e-3 + t.t0);
+}
+static GemmPlan prefill_plan(int M, int N, int K) {
+  const int kt = K / kBK;
+  GemmPlan best{1, 1};
+  double best_us = 1e30;
+  for (const TileModel& t : kTileModels) {
+    const long tm = (M + t.bm - 1) / t.bm, tn = (N + t.bn - 1) / t.bn;
+    const long tiles = tm * tn;
+    for (int sp = 1; sp <= 8; ++sp) {
+      if (sp > 1 && (kt / sp < 8 || tiles * sp > 256)) break;
+      double us = tiles_us(t, tiles * sp, (double)K / sp);
+      if (sp > 1) {  // larger fp32 epilogue, a reduce launch, partials out and back
+        const double mn = (double)M * N;
+        us += 4.0 + 2.0 + (8.0 * sp + 2.0) * mn / (sp * mn * 4.0 <= 32e6 ? 12e6 : 5e6);
+      }
+      if (us < best_us) {
+        best_us = us;
+        best = GemmPlan{t.variant, sp};
+      }
+    }
+    if (!g_gemm_tail_split || (t.variant != 1 && t.variant != 3) || tiles <= 256) continue;
+    // cut after c column tiles (whole rounds of the large tile only), the rest on a smaller tile
+    for (long c = tn - 1; c >= 1; --c) {
+      if ((tm * c) % 256 != 0 && tm * c > 256) continue;
+      const long rest = N - c * t.bn;
+      if (rest <= 0) continue;
+      for (const TileModel& u : kTileModels) {
+        if (u.variant != 1 && u.variant != 2) continue;
+        if (u.variant == 1 && t.variant == 1) continue;
+        const long tiles_u = (long)((M + u.bm - 1) / u.bm) * ((rest + u.bn - 1) / u.bn);
+        const double us = tiles_us(t, tm * c, K) + tiles_us(u, tiles_u, K) + 3.0;  // a second launch
+        if (us < best_us) {
+          best_us = us;
+          best = GemmPlan{t.variant, 1, (int)(c * t.bn), u.variant};
+        }
+      }
+    }
+  }
+  return best;
+}
+
 static GemmPlan gemm_plan(int M, int N, int K) {
   GemmPlan pl{1, 1};
+  if (M > 256 && g_gemm_variant == 0 && g_gemm_splits == 0) return prefill_plan(M, N, K);
   if (M <= 64) {
     pl.variant = 4;
   } else {
@@ -518,8 +590,8 @@ static GemmPlan gemm_plan(int M, int N, int K) {
     pl.variant = (c3 < c1 && c3 < c2) ? 3 : (c2 < c1 ? 2 : 1);
   }
   if (g_gemm_variant > 0) pl.variant = g_gemm_variant;
-  const int bm = pl.variant == 4 ? 64 : (pl.variant == 2 ? 128 : 256);
-  const int bn = pl.variant == 1 ? 160 : (pl.variant == 3 ? 256 : 128);
+  const int bm = pl.variant == 4 ? 64 : ((pl.variant == 2 || pl.variant == 5) ? 128 : 256);
+  const int bn = pl.variant == 1 ? 160 : ((pl.variant == 3 || pl.variant == 5) ? 256 : 128);
   const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
   const int kt = K / kBK;
   if (tiles < 100) {
@@ -536,40 +608,13 @@ static GemmPlan gemm_plan(int M, int N, int K) {
   return pl;
 }
 
-// Tile quantisation: a launch takes whole rounds of 256 workgroups, so 2.5 rounds cost 3.  Where it pays, the
-// product is cut at a column: the leading n1 columns keep the large tile and fill their rounds (nearly)
-// completely, the remaining ones go to a second launch on a smaller tile - 256x160 behind 256x256, or 128x128,
-// whose last round wastes a quarter as much - whichever the round count makes cheaper.  n1 = 0 leaves the launch
-// whole.  A round's cost is the tile area times a factor measured at K = 5120 (132.9 / 88.4 / 54.9 us per round
-// of 256x256 / 256x160 / 128x128 tiles: the smaller the tile, the more operand traffic per flop).
-DS_SWITCH(g_gemm_tail_split, 1);  // 0 = never cut a product at a column
-DS_SWITCH(g_gemm_tail_kind, -1);  // 0 / 1 force the 128x128 / 256x160 tile for the remainder, -1 choose by cost
-struct TailCut {
-  int n1;     // columns of the first launch (0: no cut)
-  int kind;   // tile of the second launch: 0 = 128x128, 1 = 256x160
-};
-static TailCut tail_split_columns(int M, int N, int variant) {
-  if (!g_gemm_tail_split || (variant != 1 && variant != 3)) return {0, 0};
-  const int bm = 256, bn = variant == 1 ? 160 : 256;
-  const double big = bm * bn * (variant == 1 ? 1.0 : 0.94), mid = 256 * 160 * 1.0, small = 128 * 128 * 1.55;
-  const long tm = (M + bm - 1) / bm, tn = (N + bn - 1) / bn, tm2 = (M + 127) / 128;
-  const double whole = (double)((tm * tn + 255) / 256) * big;
-  double best = whole;
-  TailCut cut = {0, 0};
-  for (long c = tn - 1; c >= 1; --c) {   // among equal costs the longest head wins
-    const long rest = N - c * bn;
-    if (rest <= 0) continue;
-    const double head = (double)((tm * c + 255) / 256) * big;
-    const double tail128 = (double)((tm2 * ((rest + 127) / 128) + 255) / 256) * small;
-    const double tail160 = (double)((tm * ((rest + 159) / 160) + 255) / 256) * mid;
-    const bool use160 = g_gemm_tail_kind < 0 ? (variant == 3 && tail160 < tail128) : g_gemm_tail_kind == 1;
-    const double cost = head + (use160 ? tail160 : tail128);
-    if (cost < best) {
-      best = cost;
-      cut = {(int)(c * bn), use160 ? 1 : 0};
-    }
-  }
-  return best < 0.95 * whole ? cut : TailCut{0, 0};  // a second launch has to earn its ramp-up
+void gemm_describe(int M, int N, int K, int* tile_rows, int* tile_cols, int* splits, int* cut_cols) {
+  static const int kBm[6] = {0, 256, 128, 256, 64, 128}, kBn[6] = {0, 160, 128, 256, 128, 256};
+  const GemmPlan pl = gemm_plan(M, N, K);
+  *tile_rows = kBm[pl.variant];
+  *tile_cols = kBn[pl.variant];
+  *splits = pl.splits;
+  *cut_cols = pl.cut_cols;
 }
 
 int gemm_splits(int M, int N, int K) {
@@ -634,21 +679,21 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
     if (fused_done) *fused_done = true;
   }
   hipError_t e;
-  const TailCut cut = (pl.splits == 1 && !p.k_cache) ? tail_split_columns(M, N, pl.variant) : TailCut{0, 0};
-  if (cut.n1 > 0) {
-    // Leading columns on the large tile in (nearly) whole rounds of 256 workgroups, the rest on a smaller tile:
-    // two launches over disjoint column ranges [0, n1) and [n1, N) of the same product (same operands, bias,
+  if (pl.cut_cols > 0 && pl.splits == 1 && !p.k_cache) {
+    // Leading columns on the large tile in whole rounds of 256 workgroups, the rest on a smaller tile: two
+    // launches over disjoint column ranges [0, cut) and [cut, N) of the same product (same operands, bias,
     // residual and output segments; only the column range differs).
     GemmParams a = p, b = p;
-    a.N = cut.n1;
-    b.n_base = cut.n1;
+    a.N = pl.cut_cols;
+    b.n_base = pl.cut_cols;
     e = pl.variant == 3 ? launch_dl<256, 256, 2, 2, 2, false>(a, 1, stream)
                         : launch_dl<256, 160, 4, 1, 3, false>(a, 1, stream);
     if (e != hipSuccess) return e;
-    if (cut.kind == 1) return launch_dl<256, 160, 4, 1, 3, false>(b, 1, stream);
+    if (pl.tail_variant == 1) return launch_dl<256, 160, 4, 1, 3, false>(b, 1, stream);
     return launch_dl<128, 128, 2, 2, 3, true>(b, 1, stream);
   }
   switch (pl.variant) {
+    case 5: e = launch_dl<128, 256, 2, 2, 3, false>(p, pl.splits, stream); break;
     case 4: e = launch_dl<64, 128, 1, 4, 3, true>(p, pl.splits, stream); break;
     case 3: e = launch_dl<256, 256, 2, 2, 2, false>(p, pl.splits, stream); break;
     case 2: e = launch_dl<128, 128, 2, 2, 3, true>(p, pl.splits, stream); break;

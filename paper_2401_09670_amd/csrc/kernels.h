@@ -51,6 +51,7 @@ struct SkinnyFused;
 // `fused` asks for extra work (see SkinnyFused); *fused_done tells whether it was carried out.
 size_t gemm_workspace_bytes(int M, int N, int K);
 int gemm_splits(int M, int N, int K);  // 1 = the launch will not split K
+void gemm_describe(int M, int N, int K, int* tile_rows, int* tile_cols, int* splits, int* cut_cols);  // the plan launch_gemm follows
 hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
                        hipStream_t stream, void* workspace = nullptr, const SkinnyFused* fused = nullptr,
                        bool* fused_done = nullptr);

@@ -94,12 +94,30 @@ def _linear_case(ctx, rows, in_f, out_f, bias, relu, residual, seed):
     (4400, 64, 4000, True, True, False),      # 18 x 16 tiles: a ragged last group of row tiles and a tile count
                                               # that is no multiple of the 256 tiles dealt out together
     (8200, 64, 1296, False, False, True),     # 33 row tiles: two full groups of 16 and a group of one
-    (2048, 64, 20480, True, True, True),      # 2.5 rounds of large tiles: cut at a column, the tail on small tiles
-    (3738, 128, 9216, True, False, True),     # the same with ragged rows (bias and residual follow the cut)
+    (2048, 64, 20480, True, True, True),      # four exact rounds of 256x160 tiles
+    (3738, 128, 9216, True, False, True),     # cut at a column with ragged rows (bias and residual follow the cut)
+    (1100, 512, 20480, True, True, False),    # 256x256 head, cut at column 12800, ragged rows
+    (512, 512, 15360, True, False, False),    # the 128x256 tile, unsplit
+    (1024, 1024, 5120, False, False, True),   # the 128x256 tile with a residual
+    (512, 5120, 5120, True, False, True),     # the 128x256 tile, K split three ways (OPT-13B out-projection at 512 rows)
+    (600, 5120, 5128, True, True, False),     # the same with ragged rows and a ragged last column tile
+    (1024, 20480, 5120, True, False, True),   # 256x160 tiles, K split in two (OPT-13B FFN-out at 1024 rows)
 ])
 def test_linear_tile_path(gpu, rows, in_f, out_f, bias, relu, residual):
     ctx = gu.make_ctx(synth.TINY)
     _linear_case(ctx, rows, in_f, out_f, bias, relu, residual, seed=rows)
+
+
+def test_linear_tile_path_cases_cover_every_plan_kind(gpu):
+    """The cases above are there for the plans they take: this pins which ones (host-side planning only)."""
+    ctx = gu.make_ctx(synth.TINY)
+    plan = lambda r, k, n: ctx.ds_linear_plan(r, k, n)
+    assert plan(512, 512, 15360) == dict(streaming=False, tile_rows=128, tile_cols=256, splits=1, cut_cols=0)
+    assert plan(512, 5120, 5120) == dict(streaming=False, tile_rows=128, tile_cols=256, splits=3, cut_cols=0)
+    assert plan(600, 5120, 5128)["splits"] > 1
+    assert plan(1024, 20480, 5120) == dict(streaming=False, tile_rows=256, tile_cols=160, splits=2, cut_cols=0)
+    assert plan(1100, 512, 20480)["cut_cols"] == 12800 and plan(3738, 128, 9216)["cut_cols"] > 0
+    assert plan(2048, 512, 5120)["tile_cols"] == 160 and plan(4400, 64, 4000)["splits"] == 1
 
 
 @pytest.mark.parametrize("rows,in_f,out_f,bias,relu,residual", [
