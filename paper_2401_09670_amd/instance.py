@@ -252,7 +252,8 @@ class GpuStack:
 
     def __init__(self, shape: synth.ModelShape, n_layers: int, seed: int, pool_blocks: int, max_batch: int,
                  max_prefill_tokens: int, max_ctx: int, max_blocks_per_seq: int, vocab: int = VOCAB,
-                 n_pos: int = N_POS, max_requests: int = 4096, overlap_handoff: bool = False, log=lambda s: None):
+                 n_pos: int = N_POS, max_requests: int = 4096, overlap_handoff: bool = False, log=lambda s: None,
+                 pool_layers: Optional[int] = None):
         import torch
         from . import binding
         if not torch.cuda.is_available():
@@ -288,7 +289,11 @@ class GpuStack:
         self.lnf_g, self.lnf_b = self._nrm((h,), 0.02, 1.0), self._nrm((h,), 0.02)
 
         self.num_blocks = int(pool_blocks)
-        pool_shape = (self.L, self.num_blocks, shape.kv_heads, shape.block_size, s)
+        # pool_layers < L is the timing-only mode: layer li uses the pool of layer li % pool_layers, so a batch
+        # whose KV does not fit beside the weights can still be stepped through the whole stack at its true
+        # shape.  Every kernel does the work it would do, the cache contents (and so the outputs) are meaningless.
+        self.pool_layers = int(pool_layers or self.L)
+        pool_shape = (self.pool_layers, self.num_blocks, shape.kv_heads, shape.block_size, s)
         self.k_pool = torch.empty(pool_shape, dtype=torch.bfloat16, device=self.dev)
         self.v_pool = torch.empty(pool_shape, dtype=torch.bfloat16, device=self.dev)
 
@@ -335,7 +340,7 @@ class GpuStack:
         idx = self._i32(pages).long()
         bs, s, nk = self.shape.block_size, self.shape.head_dim, self.shape.kv_heads
         for pool in (self.k_pool, self.v_pool):
-            for li in range(self.L):
+            for li in range(self.pool_layers):
                 blk = self.torch.empty((len(pages), nk, bs, s), dtype=self.torch.bfloat16, device=self.dev)
                 blk.normal_(0.0, 1.0, generator=self.gen)
                 pool[li].index_copy_(0, idx, blk)
@@ -372,13 +377,13 @@ class GpuStack:
                 with torch.cuda.stream(self.handoff_stream):
                     self.handoff_stream.wait_event(ready)
                     a = self._event()
-                    self.ctx.ds_kv_migrate(k_out, v_out, cu, B, t, mx, bt, table.shape[1], self.k_pool[li],
-                                           self.v_pool[li], self.num_blocks)
+                    self.ctx.ds_kv_migrate(k_out, v_out, cu, B, t, mx, bt, table.shape[1], self.k_pool[li % self.pool_layers],
+                                           self.v_pool[li % self.pool_layers], self.num_blocks)
                     mig.append((a, self._event()))
             else:
                 a = self._event()
-                self.ctx.ds_kv_migrate(k_out, v_out, cu, B, t, mx, bt, table.shape[1], self.k_pool[li],
-                                       self.v_pool[li], self.num_blocks)
+                self.ctx.ds_kv_migrate(k_out, v_out, cu, B, t, mx, bt, table.shape[1], self.k_pool[li % self.pool_layers],
+                                       self.v_pool[li % self.pool_layers], self.num_blocks)
                 mig.append((a, self._event()))
             if self.capture is not None and li in self.capture:
                 self.capture[li].append(dict(kind="prefill", lens=list(lens), x=x.clone(), y=y.clone(),
@@ -421,12 +426,12 @@ class GpuStack:
         start = self._event()
         self.ctx.ds_embed(ids, cl, self.tok_emb, self.vocab, self.pos_emb, self.n_pos, B, x)
         for li in range(self.L):
-            self.ctx.ds_decode_step(self.layers[li], x, cl, bt, B, table.shape[1], max_ctx, self.k_pool[li],
-                                    self.v_pool[li], self.num_blocks, y, self.ws_decode)
+            self.ctx.ds_decode_step(self.layers[li], x, cl, bt, B, table.shape[1], max_ctx, self.k_pool[li % self.pool_layers],
+                                    self.v_pool[li % self.pool_layers], self.num_blocks, y, self.ws_decode)
             if self.capture is not None and li in self.capture:
                 self.capture[li].append(dict(kind="decode", ctx=np.array(ctx_lens), table=np.array(table),
-                                             x=x.clone(), y=y.clone(), k_pool=self.k_pool[li].clone(),
-                                             v_pool=self.v_pool[li].clone()))
+                                             x=x.clone(), y=y.clone(), k_pool=self.k_pool[li % self.pool_layers].clone(),
+                                             v_pool=self.v_pool[li % self.pool_layers].clone()))
             x, y = y, x
         self.ctx.ds_next_token(x, None, B, self.lnf_g, self.lnf_b, self.tok_emb, self.vocab, self.next_tok, None,
                                self.ws_next)
@@ -566,6 +571,64 @@ def plan_for(cfg: dict, reqs: Sequence[Request], pool_gb: float) -> dict:
                 max_ctx=int(max(life)) * bs, max_batch=int(cfg["decode_batch"]))
 
 
+def timing_only_decode(cfg: dict, batch: int, steps: int, pool_gb: float, log=lambda s: None) -> dict:
+    """TIMING ONLY - the outputs of this run mean nothing.  Steps a decode batch of `batch` requests through the
+    whole stack at the contexts the workload recipe gives (prompt + a seeded share of the output already
+    generated), with every layer's weights resident but KV pools for only as many layers as fit `pool_gb`;
+    layer li reads and appends to the pool of layer li % pool_layers.  Each kernel streams the bytes it would
+    stream with a full set of pools (a layer's pool is far larger than the last-level cache, so re-using it a
+    few layers later gives no cache hits), which is what the time per output token depends on."""
+    import torch
+    shape, L, bs = cfg["shape"], cfg["layers"], cfg["shape"].block_size
+    p, o, seed = cfg["prompt"], cfg["output"], cfg["seed"]
+    draw = synth.lognormal_lengths if p["kind"] == "lognormal" else None
+    if draw:
+        pl = synth.lognormal_lengths(batch, p["median"], p["sigma"], p["lo"], p["hi"], seed, stream=10)
+        ol = synth.lognormal_lengths(batch, o["median"], o["sigma"], o["lo"], o["hi"], seed, stream=11)
+    else:
+        pl = synth.uniform_lengths(batch, p["lo"], p["hi"], seed, stream=10)
+        ol = synth.uniform_lengths(batch, o["lo"], o["hi"], seed, stream=11)
+    frac = np.random.Generator(np.random.Philox(key=[seed, 7012])).random(batch)
+    ctx0 = (pl + np.floor(frac * np.maximum(ol - 1, 0))).astype(np.int32)      # tokens cached when timing starts
+    cap = ctx0 + steps
+    table, nblk = synth.make_block_tables([int(c) for c in cap], bs, seed)
+    layer_bytes = 2 * 2 * shape.kv_heads * shape.head_dim * bs * nblk
+    pool_layers = int(max(1, min(L, pool_gb * 1e9 // layer_bytes)))
+    log(f"timing-only: batch {batch}, contexts {int(ctx0.min())}..{int(ctx0.max())} (mean {ctx0.mean():.0f}), "
+        f"{nblk} pages = {layer_bytes / 1e9:.2f} GB per layer, pools for {pool_layers} of {L} layers")
+    stack = GpuStack(shape, L, seed, nblk, batch, 0, int(cap.max()) + 1, table.shape[1], max_requests=batch,
+                     log=log, pool_layers=pool_layers)
+    stack.k_pool.normal_(0.0, 1.0, generator=stack.gen)
+    stack.v_pool.normal_(0.0, 1.0, generator=stack.gen)
+    stack.cur_tok.copy_(torch.randint(0, stack.vocab, (batch,), generator=stack.gen, device=stack.dev,
+                                      dtype=torch.int32))
+    rows = list(range(batch))
+    ev = []
+    for j in range(steps + 2):                                   # two untimed steps first
+        ev.append((ctx0 + max(j - 2, 0), stack.decode_step(rows, ctx0 + max(j - 2, 0), table)))
+    torch.cuda.synchronize()
+    S = [dict(batch=batch, kv_tokens=int(c.sum()) + batch, ctx=c, ms=a.elapsed_time(b)) for c, (a, b) in ev[2:]]
+    res = summarise(dict(prefills=[], steps=S, wall_s=0.0, finished=0), shape, L)["decode"]
+    res.update(pool_layers=pool_layers, layers=L, layer_kv_gb=layer_bytes / 1e9, ctx_min=int(ctx0.min()),
+               ctx_max=int(ctx0.max()))
+    return res
+
+
+def timing_only_markdown(cfg: dict, r: dict, cmd: str) -> str:
+    return "\n".join([
+        f"## Timing-only: decode batch {int(r['mean_batch'])} through all {r['layers']} layers (outputs meaningless)", "",
+        f"Produced by `{cmd}`.  The KV of this batch ({r['layer_kv_gb']:.2f} GB per layer, "
+        f"{r['layer_kv_gb'] * r['layers']:.0f} GB over the stack) does not fit beside the weights; layer li uses the "
+        f"pool of layer li mod {r['pool_layers']} (random contents).  Every kernel runs at its true shape and streams "
+        "its true byte count; only the cache contents, hence the generated tokens, are meaningless.", "",
+        "| decoding (timing only) | value |", "|---|---|",
+        f"| steps / contexts | {r['steps']} / {r['ctx_min']}..{r['ctx_max']}, mean {r['mean_ctx']:.0f} |",
+        f"| time per output token (one whole-stack step) | **mean {r['tpot_ms_mean']:.2f} ms**, P50 "
+        f"{r['tpot_ms_p50']:.2f}, P90 {r['tpot_ms_p90']:.2f} |",
+        f"| decode rate | {r['tokens_per_s']:.0f} tokens/s |",
+        f"| algorithmic HBM rate | {r['gb_per_s']:.0f} GB/s = {100 * r['hbm_frac']:.1f} % of HBM peak |", ""])
+
+
 def to_markdown(cfg: dict, plan: dict, n_req: int, res: dict, cmd: str) -> str:
     shape, L = cfg["shape"], cfg["layers"]
     lines = [f"# Whole-stack run: {cfg['name']} ({L} layers, h = {shape.hidden}, {shape.n_heads} x {shape.head_dim}, "
@@ -614,10 +677,26 @@ def main(argv=None) -> int:
     ap.add_argument("--overlap-handoff", action="store_true",
                     help="run each layer's KV hand-off on a second stream beside the next layer's prefill")
     ap.add_argument("--out", type=str, default="")
+    ap.add_argument("--timing-only-batch", type=int, default=0,
+                    help="TIMING ONLY: step a decode batch of this size through the whole stack with KV pools for as "
+                         "many layers as fit (layers share pools; outputs are meaningless), instead of the workload")
     a = ap.parse_args(argv)
     cfg = dict(synth.config(a.config - 1))
     if a.layers:
         cfg["layers"] = a.layers
+    if a.timing_only_batch:
+        sh, Lt = cfg["shape"], cfg["layers"]
+        wgb = Lt * 2.0 * (sh.hidden * sh.qkv_width + sh.hidden ** 2 + 2 * sh.hidden * sh.ffn) / 1e9
+        r = timing_only_decode(cfg, a.timing_only_batch, a.max_steps or 16, a.pool_gb or max(8.0, 250.0 - wgb),
+                               log=lambda s: print(f"[instance] {s}", flush=True))
+        md = timing_only_markdown(cfg, r, "python -m paper_2401_09670_amd.instance "
+                                  + " ".join(argv if argv is not None else sys.argv[1:]))
+        print(md)
+        print(json.dumps(r, default=float))
+        if a.out:
+            with open(a.out, "w") as f:
+                f.write(md)
+        return 0
     n_req = a.requests or {3: 512, 4: 48, 5: 0}[a.config]
     reqs = requests_for(cfg, n_req)
     shape, L = cfg["shape"], cfg["layers"]

@@ -192,3 +192,25 @@ def test_small_stack_decodes_preloaded_contexts(gpu):
         for c in caps:
             assert np.all(np.isfinite(gu.to_f64(c["y"])))
             _check_decode_capture(stack, li, c, list(range(len(ctxs))), np.float64)
+
+
+def test_timing_only_mode_cycles_layers_through_fewer_pools(gpu):
+    """The labelled timing-only mode (a decode batch whose KV does not fit beside the weights: layers share a
+    few pools, outputs are meaningless) on a small stack: it runs every layer at the recipe's contexts, uses
+    fewer pools than layers, and prices the step with the bytes of the full batch."""
+    shape = synth.ModelShape(hidden=512, n_heads=4, head_dim=128, ffn=2048)
+    cfg = dict(name="tiny-summarization", shape=shape, seed=99, layers=5,
+               prompt=dict(kind="uniform", lo=100, hi=400), output=dict(kind="uniform", lo=4, hi=32))
+    batch, steps = 12, 3
+    one_layer_gb = 2 * 2 * shape.kv_heads * shape.head_dim * 16 * (batch * 28) / 1e9      # >= this batch's pages
+    r = inst.timing_only_decode(cfg, batch, steps, pool_gb=2.5 * one_layer_gb)
+    assert 1 <= r["pool_layers"] < cfg["layers"]
+    assert r["steps"] == steps and r["mean_batch"] == batch
+    assert 100 <= r["ctx_min"] <= r["ctx_max"] <= 400 + 31
+    assert np.isfinite(r["tpot_ms_mean"]) and r["tpot_ms_mean"] > 0
+    # the byte count behind the HBM fraction is that of all five layers at the batch's real contexts
+    ctx = np.full(batch, r["mean_ctx"] - 1)
+    per_step = inst.decode_bytes(ctx, shape, cfg["layers"], inst.VOCAB)
+    assert abs(r["gb_per_s"] * 1e9 * r["tpot_ms_mean"] * 1e-3 / per_step - 1) < 0.05
+    md = inst.timing_only_markdown(cfg, r, "cmd")
+    assert "outputs meaningless" in md and "mod %d" % r["pool_layers"] in md
