@@ -469,9 +469,11 @@ static double tile_cost(int M, int N, int BM, int BN, double factor) {
 DS_SWITCH(g_gemm_variant, 0);     // 0 = cost model, 1..5 force a tile
 DS_SWITCH(g_gemm_splits, 0);      // 0 = plan, > 0 force the split count
 DS_SWITCH(g_gemm_tail_split, 1);  // 0 = never cut a product at a column
+DS_SWITCH(g_gemm_cut_cols, 0);    // > 0: cut at this column ...
+DS_SWITCH(g_gemm_tail_kind, 0);   // ... with this tile for the rest (1, 2, 7)
 
 struct GemmPlan {
-  int variant;  // 1: 256x160, 2: 128x128, 3: 256x256, 4: 64x128, 5: 128x256
+  int variant;  // 1: 256x160, 2: 128x128, 3: 256x256, 4: 64x128, 5: 128x256 (7: 256x128, behind a cut only)
   int splits;
   int cut_cols = 0;     // > 0: the product is cut at this column; [0, cut_cols) on `variant`, the rest on ...
   int tail_variant = 0; // ... this tile, as a second launch
@@ -531,7 +533,13 @@ struct TileModel {
   double us_per_kk, t0;
 };
 static const TileModel kTileModels[] = {{3, 256, 256, 24.2, 11.6}, {1, 256, 160, 16.5, 7.9},
-                                        {5, 128, 256, 15.0, 8.0}, {2, 128, 128, 11.5, 6.0}};
+                                        {5, 128, 256, 15.0, 8.0}, {2, 128, 128, 11.5, 6.0},
+                                        // for the columns behind a cut only: FFN-in of OPT-13B at 2048 rows ends
+                                        // on 4096 columns = one exact round of 256x128 tiles (355 us for the
+                                        // product against 362 us with 208 tiles of 256x160).  (A 256x224 tile,
+                                        // which makes QKV two exact rounds of 8192 + 7168 columns, measured 2 %
+                                        // slower than 1.875 rounds of 256x256 tiles: not kept.)
+                                        {7, 256, 128, 14.5, 7.0}};
 // time of `tiles` workgroups of tile t over K (one launch, no split)
 static double tiles_us(const TileModel& t, long tiles, double K) {
   const double exact = tiles / 256.0, full = (double)((tiles + 255) / 256);
@@ -543,6 +551,7 @@ static GemmPlan prefill_plan(int M, int N, int K) {
   GemmPlan best{1, 1};
   double best_us = 1e30;
   for (const TileModel& t : kTileModels) {
+    if (t.variant > 5) continue;
     const long tm = (M + t.bm - 1) / t.bm, tn = (N + t.bn - 1) / t.bn;
     const long tiles = tm * tn;
     for (int sp = 1; sp <= 8; ++sp) {
@@ -564,8 +573,9 @@ static GemmPlan prefill_plan(int M, int N, int K) {
       const long rest = N - c * t.bn;
       if (rest <= 0) continue;
       for (const TileModel& u : kTileModels) {
-        if (u.variant != 1 && u.variant != 2) continue;
+        if (u.variant != 1 && u.variant != 2 && u.variant != 7) continue;
         if (u.variant == 1 && t.variant == 1) continue;
+        if (u.bn > t.bn) continue;
         const long tiles_u = (long)((M + u.bm - 1) / u.bm) * ((rest + u.bn - 1) / u.bn);
         const double us = tiles_us(t, tm * c, K) + tiles_us(u, tiles_u, K) + 3.0;  // a second launch
         if (us < best_us) {
@@ -575,6 +585,7 @@ static GemmPlan prefill_plan(int M, int N, int K) {
       }
     }
   }
+  if (g_gemm_cut_cols > 0 && g_gemm_cut_cols < N) best = GemmPlan{3, 1, g_gemm_cut_cols, g_gemm_tail_kind};
   return best;
 }
 
@@ -689,8 +700,11 @@ hipError_t launch_gemm(const void* X, const void* W, int M, int N, int K, const 
     e = pl.variant == 3 ? launch_dl<256, 256, 2, 2, 2, false>(a, 1, stream)
                         : launch_dl<256, 160, 4, 1, 3, false>(a, 1, stream);
     if (e != hipSuccess) return e;
-    if (pl.tail_variant == 1) return launch_dl<256, 160, 4, 1, 3, false>(b, 1, stream);
-    return launch_dl<128, 128, 2, 2, 3, true>(b, 1, stream);
+    switch (pl.tail_variant) {
+      case 1: return launch_dl<256, 160, 4, 1, 3, false>(b, 1, stream);
+      case 7: return launch_dl_epi<256, 128, 4, 1, 3, kEpiPlain>(b, 1, stream);
+      default: return launch_dl<128, 128, 2, 2, 3, true>(b, 1, stream);
+    }
   }
   switch (pl.variant) {
     case 5: e = launch_dl<128, 256, 2, 2, 3, false>(p, pl.splits, stream); break;

@@ -97,6 +97,7 @@ def _linear_case(ctx, rows, in_f, out_f, bias, relu, residual, seed):
     (2048, 64, 20480, True, True, True),      # four exact rounds of 256x160 tiles
     (3738, 128, 9216, True, False, True),     # cut at a column with ragged rows (bias and residual follow the cut)
     (1100, 512, 20480, True, True, False),    # 256x256 head, cut at column 12800, ragged rows
+    (2048, 1024, 20480, True, True, False),   # two rounds of 256x256 tiles, the last 4096 columns on 256x128 tiles
     (512, 512, 15360, True, False, False),    # the 128x256 tile, unsplit
     (1024, 1024, 5120, False, False, True),   # the 128x256 tile with a residual
     (512, 5120, 5120, True, False, True),     # the 128x256 tile, K split three ways (OPT-13B out-projection at 512 rows)
@@ -117,6 +118,7 @@ def test_linear_tile_path_cases_cover_every_plan_kind(gpu):
     assert plan(600, 5120, 5128)["splits"] > 1
     assert plan(1024, 20480, 5120) == dict(streaming=False, tile_rows=256, tile_cols=160, splits=2, cut_cols=0)
     assert plan(1100, 512, 20480)["cut_cols"] == 12800 and plan(3738, 128, 9216)["cut_cols"] > 0
+    assert plan(2048, 1024, 20480)["cut_cols"] == 16384
     assert plan(2048, 512, 5120)["tile_cols"] == 160 and plan(4400, 64, 4000)["splits"] == 1
 
 
