@@ -33,51 +33,55 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint16_t* _
   const uint16_t* xr = x + (row_index ? (size_t)row_index[row] : row) * (size_t)h;
   uint16_t* orow = out + row * (size_t)h;
 
+  // Every load of the kernel is issued before anything waits: the row's pieces with their index clamped into
+  // the row (a thread past the end re-reads the last piece and its values are masked out of the sums - with
+  // the loads under per-thread predicates the compiler waited for each one before issuing the next, three
+  // memory latencies in a row for a 5120-wide row), and the gain / shift pieces, which depend on nothing.
+  u32x4 raw[NCH], g[NCH], b[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) raw[i] = ld16(xr + min((int)threadIdx.x + i * kLnThreads, nchunk - 1) * 8);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = min((int)threadIdx.x + i * kLnThreads, nchunk - 1);
+    g[i] = ld16(gamma + c * 8);
+    b[i] = ld16(beta + c * 8);
+  }
   float vals[NCH][8];
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
-    const int c = threadIdx.x + i * kLnThreads;
-    if (c < nchunk) {
-      const u32x4 raw = ld16(xr + c * 8);
+    const bool live = (int)threadIdx.x + i * kLnThreads < nchunk;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        vals[i][2 * j] = bf16_lo(raw[j]);
-        vals[i][2 * j + 1] = bf16_hi(raw[j]);
-        sum += vals[i][2 * j] + vals[i][2 * j + 1];
-      }
+    for (int j = 0; j < 4; ++j) {
+      vals[i][2 * j] = bf16_lo(raw[i][j]);
+      vals[i][2 * j + 1] = bf16_hi(raw[i][j]);
+      sum += live ? vals[i][2 * j] + vals[i][2 * j + 1] : 0.f;
     }
   }
   const float mean = block_sum(sum, red) / (float)h;
   float sq = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
-    const int c = threadIdx.x + i * kLnThreads;
-    if (c < nchunk) {
+    const bool live = (int)threadIdx.x + i * kLnThreads < nchunk;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float d = vals[i][j] - mean;
-        sq += d * d;
-      }
+    for (int j = 0; j < 8; ++j) {
+      const float d = vals[i][j] - mean;
+      sq += live ? d * d : 0.f;
     }
   }
   const float var = block_sum(sq, red) / (float)h;
   const float rstd = rsqrtf(var + eps);
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
-    const int c = threadIdx.x + i * kLnThreads;
-    if (c < nchunk) {
-      const u32x4 g = ld16(gamma + c * 8);
-      const u32x4 b = ld16(beta + c * 8);
-      u32x4 o;
+    const int c = (int)threadIdx.x + i * kLnThreads;
+    u32x4 o;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float lo = (vals[i][2 * j] - mean) * rstd * bf16_lo(g[j]) + bf16_lo(b[j]);
-        const float hi = (vals[i][2 * j + 1] - mean) * rstd * bf16_hi(g[j]) + bf16_hi(b[j]);
-        o[j] = pack_bf16(lo, hi);
-      }
-      st16(orow + c * 8, o);
+    for (int j = 0; j < 4; ++j) {
+      const float lo = (vals[i][2 * j] - mean) * rstd * bf16_lo(g[i][j]) + bf16_lo(b[i][j]);
+      const float hi = (vals[i][2 * j + 1] - mean) * rstd * bf16_hi(g[i][j]) + bf16_hi(b[i][j]);
+      o[j] = pack_bf16(lo, hi);
     }
+    if (c < nchunk) st16(orow + c * 8, o);
   }
 }
 
