@@ -20,12 +20,28 @@ constexpr int kAttQ = 128;    // queries per workgroup
 constexpr int kAttKV = 64;    // keys per tile
 constexpr float kSlack = 8.f;   // exponent headroom before the softmax reference point is moved
 
+#ifdef DS_DEV_SWITCHES
+// timing harness builds only: 16 wall-clock stamps (100 MHz) per workgroup - entry, first tile landed, the end
+// of each of the first 12 tiles, exit - and the tile count
+unsigned long long* g_attn_dbg = nullptr;
+#define DS_ATT_DBG_PARAM , unsigned long long* dbg
+#define DS_ATT_DBG_ARG , g_attn_dbg
+#define DS_ATT_STAMP(i)                                                                          \
+  do {                                                                                           \
+    if (dbg && threadIdx.x == 0) dbg[(size_t)blockIdx.x * 16 + (i)] = __builtin_amdgcn_s_memrealtime(); \
+  } while (0)
+#else
+#define DS_ATT_DBG_PARAM
+#define DS_ATT_DBG_ARG
+#define DS_ATT_STAMP(i)
+#endif
+
 template <int HD>
 __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))) void prefill_attention_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ cu_seqlens, uint16_t* __restrict__ o, int n_heads, int kv_group,
     float scale_log2e,
-    int n_pairs, int pairs_per_xcd, int n_qt, int qt_fast) {
+    int n_pairs, int pairs_per_xcd, int n_qt, int qt_fast DS_ATT_DBG_PARAM) {
   constexpr int DSTEPS = HD / 16;   // MFMA k-steps over the head dimension
   constexpr int DT = HD / 32;       // 32-row tiles of O^T
   constexpr int CPR = HD / 8;       // 16-byte chunks per K/V row
@@ -55,6 +71,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
   const int len = cu_seqlens[seq + 1] - start;
   const int q0 = (n_qt - 1 - rank) * kAttQ;  // heaviest query tile (most keys) first
   if (q0 >= len) return;
+  DS_ATT_STAMP(0);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -133,6 +150,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
   request(0, 0);
   wait_loads();
   __syncthreads();
+  DS_ATT_STAMP(1);
 
   const int kswz = CPR == 16 ? (lq & 15) : ((lq >> 1) & 7);   // K fragment rows are u*32 + lq
   for (int tile = 0; tile < n_tiles; ++tile) {
@@ -146,6 +164,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
     if (kv0 > qw0 + 31 || qw0 >= len) {
       wait_loads();
       __syncthreads();
+      if (tile < 12) DS_ATT_STAMP(2 + tile);
       continue;
     }
 
@@ -265,6 +284,7 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
       }
     wait_loads();     // this wave's share of tile i+1 has landed
     __syncthreads();  // ... and everybody's; and every wave is done reading tile i
+    if (tile < 12) DS_ATT_STAMP(2 + tile);
   }
 
   // ---- normalise and store: lane holds O[my_q][32d + 8g + 4hl + i] ----
@@ -282,6 +302,10 @@ __global__ __launch_bounds__(kAttThreads) __attribute__((amdgpu_waves_per_eu(2))
         *reinterpret_cast<u32x2*>(orow + d * 32 + g * 8) = w;
       }
   }
+  DS_ATT_STAMP(14);
+#ifdef DS_DEV_SWITCHES
+  if (dbg && threadIdx.x == 0) dbg[(size_t)blockIdx.x * 16 + 15] = (unsigned long long)n_tiles;
+#endif
 }
 
 DS_SWITCH(g_attn_force_order, -1);  // 0/1 force the workgroup order, -1 choose by grid size
@@ -307,11 +331,11 @@ hipError_t launch_prefill_attention(const void* q, const void* k, const void* v,
     (void)KernelAttrReg<prefill_attention_kernel<128>, 2 * 2 * kAttKV * 128 * (int)sizeof(uint16_t)>::done;
     hipLaunchKernelGGL(prefill_attention_kernel<128>, grid, dim3(kAttThreads), lds_bytes, stream, (const uint16_t*)q,
                        (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, kv_group, scale_log2e,
-                       (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast);
+                       (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast DS_ATT_DBG_ARG);
   } else if (head_dim == 64) {
     hipLaunchKernelGGL(prefill_attention_kernel<64>, grid, dim3(kAttThreads), lds_bytes, stream, (const uint16_t*)q,
                        (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, (uint16_t*)o, n_heads, kv_group, scale_log2e,
-                       (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast);
+                       (int)n_pairs, (int)pairs_per_xcd, n_qt, qt_fast DS_ATT_DBG_ARG);
   } else {
     return hipErrorInvalidValue;
   }
