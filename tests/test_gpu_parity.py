@@ -404,3 +404,51 @@ def test_decode_step_replays_identically_from_a_hip_graph(gpu):
         torch.cuda.synchronize()
         assert torch.equal(y, want_y), j
         assert torch.equal(kc, want_k) and torch.equal(vc, want_v), j
+
+
+def test_prefill_and_handoff_replay_identically_from_a_hip_graph(gpu):
+    """The prefill pass and the KV hand-off behind it, captured together: ragged prompts (tile, split-K and
+    ragged-page paths), three replays, each after eager work that changes the input and clears the outputs."""
+    shape = synth.ModelShape(hidden=1024, n_heads=8, head_dim=128, ffn=4096)
+    seed, lens = 1812, [300, 77, 513]
+    t, h = sum(lens), shape.hidden
+    ctx = gu.make_ctx(shape)
+    lw, keep = gu.weights_to_dev(synth.make_layer_weights(shape, seed))
+    cu = gu.i32_dev(synth.cu_seqlens(lens))
+    bt, nblk = synth.make_block_tables([l + 16 for l in lens], 16, seed)
+    bt_d = gu.i32_dev(bt)
+    x = torch.empty(t, h, dtype=torch.bfloat16, device="cuda")
+    y, k_out, v_out = torch.empty_like(x), torch.empty_like(x), torch.empty_like(x)
+    kc = torch.empty(nblk, shape.n_heads, 16, shape.head_dim, dtype=torch.bfloat16, device="cuda")
+    vc = torch.empty_like(kc)
+    ws = gu.workspace(ctx.ds_prefill_workspace_bytes(t))
+
+    def step():
+        ctx.ds_prefill(lw, x, cu, len(lens), t, max(lens), y, k_out, v_out, ws)
+        ctx.ds_kv_migrate(k_out, v_out, cu, len(lens), t, max(lens), bt_d, bt.shape[1], kc, vc, nblk)
+
+    def eager(j):
+        x.copy_(gu.to_dev(synth.make_activations(t, h, seed, stream=40 + j)))
+        for buf in (y, k_out, v_out, kc, vc):
+            buf.fill_(float(j))
+
+    eager(0)
+    step()                                  # warm-up outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for j in range(1, 4):
+        eager(j)
+        step()
+        torch.cuda.synchronize()
+        want = [b.clone() for b in (y, k_out, v_out, kc, vc)]
+        eager(j)
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, w, name in zip((y, k_out, v_out, kc, vc), want, ("y", "k_out", "v_out", "k_cache", "v_cache")):
+            assert torch.equal(got, w), (j, name)

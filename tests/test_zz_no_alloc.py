@@ -65,6 +65,51 @@ def test_static_scratch_decode_step_matches_workspace_decode_step(gpu):
     assert torch.equal(got2b[0], want2[0]) and torch.equal(got1b[0], want1[0])
 
 
+def test_static_scratch_decode_step_replays_from_a_hip_graph(gpu):
+    """What the entry point is for: a decode step captured into a HIP graph with no workspace to carry.  Three
+    replays, each after eager work that changes the inputs, against ds_decode_step run eagerly on the same inputs."""
+    shape = synth.ModelShape(hidden=1024, n_heads=8, head_dim=128, ffn=4096)
+    seed = 2718
+    ctx = gu.make_ctx(shape)
+    lw, keep = gu.weights_to_dev(synth.make_layer_weights(shape, seed))
+    c = _case(ctx, lw, shape, seed, [200 + 7 * i for i in range(24)])
+    x, lens = c["x"].clone(), c["lens"].clone()
+    kc, vc = c["kc0"].clone(), c["vc0"].clone()
+    y = torch.empty_like(x)
+    ws = gu.workspace(ctx.ds_decode_workspace_bytes(c["B"], c["max_ctx"]))
+
+    def static_step():
+        ctx.ds_decode_step_static(lw, x, lens, c["bt"], c["B"], c["max_blocks"], c["max_ctx"], kc, vc, c["nblk"], y)
+
+    def eager(j):
+        x.copy_(gu.to_dev(synth.make_activations(c["B"], shape.hidden, seed, stream=20 + j)))
+        lens.copy_(c["lens"] - j)           # shorter contexts: still inside every sequence's pages
+        kc.copy_(c["kc0"])
+        vc.copy_(c["vc0"])
+        y.zero_()
+
+    eager(0)
+    static_step()                           # warm-up outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            static_step()
+    torch.cuda.synchronize()
+    for j in range(1, 4):
+        eager(j)
+        ctx.ds_decode_step(lw, x, lens, c["bt"], c["B"], c["max_blocks"], c["max_ctx"], kc, vc, c["nblk"], y, ws)
+        torch.cuda.synchronize()
+        want_y, want_k, want_v = y.clone(), kc.clone(), vc.clone()
+        eager(j)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want_y), j
+        assert torch.equal(kc, want_k) and torch.equal(vc, want_v), j
+
+
 def test_static_scratch_rejects_what_does_not_fit(gpu):
     shape = synth.OPT_13B
     ctx = gu.make_ctx(shape)
