@@ -189,8 +189,9 @@ ds_status ds_layernorm(ds_ctx *ctx, const void *x, const void *gamma, const void
  * needed for this shape). */
 size_t ds_linear_workspace_bytes(const ds_ctx *ctx, int32_t rows, int32_t in_f, int32_t out_f);
 /* Which kernel a ds_linear call of this shape takes (host-side planning only, nothing is launched):
- * *streaming = 1 for the weight-streaming kernels of the decode phase (then tile_rows = tile_cols = 0),
- * 0 for the MFMA tile kernel with tiles of tile_rows x tile_cols outputs; *splits = workgroups the
+ * *streaming = 1 for the weight-streaming kernels of the decode phase (then tile_rows = 0 and tile_cols =
+ * output columns per workgroup), 0 for the MFMA tile kernel with tiles of tile_rows x tile_cols outputs;
+ * *splits = workgroups the
  * reduction dimension is split over (1 = not split; a split launch is followed by a reduce pass);
  * *cut_cols > 0 = the output columns from there on run as a second launch on a smaller tile.
  * App. A.2 / A.3 give the product shapes; the plan is this library's answer to how many tokens it takes

@@ -16,16 +16,25 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
          "-Wno-unused-command-line-argument"]
 
 
-def build_library(verbose: bool = False, jobs: int = 8) -> str:
-    """Compile every kernel source and link libds.so.  Always recompiles."""
-    obj_dir = os.path.join(PKG_DIR, "_build")
+DEV_LIB_PATH = os.path.join(PKG_DIR, "libds_dev.so")
+
+
+def build_library(verbose: bool = False, jobs: int = 8, dev: bool = False) -> str:
+    """Compile every kernel source and link libds.so.  Always recompiles.
+
+    dev=True builds libds_dev.so instead: the same sources with -DDS_DEV_SWITCHES, in which the planning
+    choices (tile shape, split count, column cut, kernel family) can be forced at run time through
+    ds_dev_switch.  Only the sweep harness (plan_sweep.py) loads it; the product never does."""
+    obj_dir = os.path.join(PKG_DIR, "_build_dev" if dev else "_build")
+    lib_path = DEV_LIB_PATH if dev else LIB_PATH
+    flags = FLAGS + (["-DDS_DEV_SWITCHES"] if dev else [])
     os.makedirs(obj_dir, exist_ok=True)
     procs = []
     objs = []
     for src in SOURCES:
         obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [HIPCC, *flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -42,10 +51,10 @@ def build_library(verbose: bool = False, jobs: int = 8) -> str:
             print(f"--- {src}\n" + "\n".join(lines))
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs]
     subprocess.run(cmd, check=True)
-    return LIB_PATH
+    return lib_path
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_library(verbose=True, dev="--dev" in sys.argv[1:]))

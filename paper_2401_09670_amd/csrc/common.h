@@ -8,7 +8,14 @@
 // build, so the choice logic they sit in folds away; the timing harnesses compile the sources with
 // -DDS_DEV_SWITCHES and flip them at run time.
 #ifdef DS_DEV_SWITCHES
-#define DS_SWITCH(name, value) int name = value
+namespace ds {
+struct SwitchReg {  // makes a switch settable by name through ds_dev_switch (development builds only)
+  SwitchReg(const char* name, int* value);
+};
+}  // namespace ds
+#define DS_SWITCH(name, value) \
+  int name = value;            \
+  static ::ds::SwitchReg switch_reg_##name(#name, &name)
 #else
 #define DS_SWITCH(name, value) static constexpr int name = value
 #endif

@@ -57,6 +57,35 @@ hipError_t configure_kernels() {
 // copies are given the per-device address kept in DeviceState::scratch, never the name.
 static __device__ __align__(256) unsigned char scratch[DS_STATIC_SCRATCH_BYTES];
 
+#ifdef DS_DEV_SWITCHES
+#include "common.h"
+// Development builds: the planning switches by name (the sweep harness sets them through ds_dev_switch).
+namespace ds {
+namespace {
+struct SwitchEntry {
+  const char* name;
+  int* value;
+};
+std::vector<SwitchEntry>& switch_table() {
+  static std::vector<SwitchEntry> t;
+  return t;
+}
+}  // namespace
+SwitchReg::SwitchReg(const char* name, int* value) { switch_table().push_back({name, value}); }
+}  // namespace ds
+
+// Sets switch `name` to `value`; returns its previous value, or INT32_MIN if there is no such switch.
+extern "C" int32_t ds_dev_switch(const char* name, int32_t value) {
+  for (auto& e : ds::switch_table())
+    if (strcmp(e.name, name) == 0) {
+      const int32_t old = *e.value;
+      *e.value = value;
+      return old;
+    }
+  return INT32_MIN;
+}
+#endif
+
 namespace {
 
 constexpr int kMaxDevices = 64;
@@ -421,8 +450,9 @@ ds_status ds_linear_plan(const ds_ctx* ctx, int32_t rows, int32_t in_f, int32_t 
   *tile_rows = *tile_cols = *cut_cols = 0;
   *splits = 1;
   if (*streaming) {
-    const size_t ws = ds::skinny_workspace_bytes(rows, out_f, in_f);
-    *splits = ws ? (int32_t)(ws / ((size_t)rows * out_f * sizeof(float))) : 1;
+    int tc, sp;
+    ds::skinny_describe(rows, out_f, in_f, &tc, &sp);
+    *tile_cols = tc; *splits = sp;
   } else {
     int tr, tc, sp, cut;
     ds::gemm_describe(rows, out_f, in_f, &tr, &tc, &sp, &cut);

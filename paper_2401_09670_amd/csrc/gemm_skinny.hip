@@ -657,7 +657,7 @@ struct SkinnyPlan {
 // (<= 256 workgroups) and should fill it; among such plans take the fewest bytes through the CUs' L1:
 //   weights + (N/BN) * X (each column block re-reads the activations) + partial sums written and
 //   read back.
-static SkinnyPlan skinny_plan(int M, int N, int K, bool allow_split = true) {
+static SkinnyPlan skinny_plan(int M, int N, int K, bool allow_split = true, double* cost_out = nullptr) {
   const int slabs = K / kSkKS;
   const int mp = M <= 64 ? 64 : (M <= 128 ? 128 : 256);
   SkinnyPlan best{1, 1};
@@ -674,13 +674,14 @@ static SkinnyPlan skinny_plan(int M, int N, int K, bool allow_split = true) {
       const double wgs = (double)wgs_n * splits;
       const bool forced = g_skinny_force_splits > 0;
       if (wgs > 256.0 && splits > 1 && !forced) break;        // never split into a second round
-      const double rounds = wgs <= 256.0 ? 1.0 : wgs / 256.0;  // unsplit but larger than the chip
+      const double rounds = wgs <= 256.0 ? 1.0 : ceil(wgs / 256.0);  // unsplit but larger than the chip: whole rounds
       const double fill = wgs >= 256.0 ? 1.0 : 256.0 / wgs;    // idle CUs stretch the time
       // partial sums are charged four times their bytes: they are stored by every workgroup at once at
       // the end of the launch and read back by a second, latency-bound launch (measured: 6 splits of
-      // 128 columns beat 12 splits of 256 on the FFN-out shape although they stream more activations)
+      // 128 columns beat 12 splits of 256 on the FFN-out shape although they stream more activations; charged
+      // for the padded row count, since a workgroup's partial-tile epilogue costs the same at 16 rows as at 64)
       const double bytes = 2.0 * N * K + 2.0 * wgs_n * (double)mp * K +
-                           (splits > 1 ? 4.0 * 2.0 * 4.0 * splits * (double)M * N : 0.0);
+                           (splits > 1 ? 4.0 * 2.0 * 4.0 * splits * (double)mp * N : 0.0);
       const double cost = bytes * fill * rounds;
       if (cost < best_cost) {
         best_cost = cost;
@@ -688,6 +689,7 @@ static SkinnyPlan skinny_plan(int M, int N, int K, bool allow_split = true) {
       }
     }
   }
+  if (cost_out) *cost_out = best_cost + (best.splits > 1 ? 57e6 : 0.0);  // + the reduce launch (6 us of the chip)
   return best;
 }
 
@@ -748,7 +750,22 @@ static int wring_tiles(int M, int N, int K) {
   const int nt = r5 < r4 ? 5 : 4;
   const int tiles = nt == 5 ? t5 : t4;
   if (M > 64 && nt != 5) return 0;
-  return tiles >= 160 ? nt : 0;
+  if (tiles < 160) return 0;
+  // Several rounds of workgroups: each of them streams the activation slab again beside its 64 or 80 weight
+  // rows, and from 32 rows up that is as many bytes through a compute unit's load path as the weights.  The
+  // split-K ring kernel with 256-column tiles reads a quarter of that and stays within one round; it wins where
+  // its bytes (in skinny_plan's terms, reduce launch included) are clearly fewer.  Measured at 64 rows: FFN-in of
+  // OPT-175B 245 -> 214 us, QKV of OPT-66B 107 -> 98 us; QKV of OPT-175B and FFN-in of OPT-66B (two rounds of 80
+  // columns against 144 workgroups of 256) stay here, 6-9 % ahead.
+  const int rounds = nt == 5 ? r5 : r4;
+  if (rounds > 1 && M > 16) {
+    const double rows = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
+    const double wring_cost = rounds * 256.0 * (16.0 * nt + rows) * K * 2.0;
+    double ring_cost;
+    skinny_plan(M, N, K, true, &ring_cost);
+    if (ring_cost < 0.95 * wring_cost) return 0;
+  }
+  return nt;
 }
 
 static hipError_t dispatch_skinny(const SkinnyParams& p, const SkinnyPlan& pl, hipStream_t stream) {
@@ -839,6 +856,19 @@ hipError_t launch_splitk_reduce(const float* partial, int splits, int M, int N, 
     hipLaunchKernelGGL(skinny_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p, splits);
   }
   return hipGetLastError();
+}
+
+// What launch_skinny_gemm does for a plain product of this shape: columns per workgroup and splits over K
+// (1 split and 64 or 80 columns = the unsplit kernel with wave-private rings).
+void skinny_describe(int M, int N, int K, int* tile_cols, int* splits) {
+  if (const int nt = wring_tiles(M, N, K)) {
+    *tile_cols = 16 * nt;
+    *splits = 1;
+    return;
+  }
+  const SkinnyPlan pl = skinny_plan(M, N, K);
+  *tile_cols = 64 * pl.ntw;
+  *splits = pl.splits;
 }
 
 hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,

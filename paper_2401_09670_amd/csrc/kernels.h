@@ -82,6 +82,7 @@ hipError_t launch_splitk_reduce(const float* partial, int splits, int M, int N, 
 // `*fused_done` tells whether the requested fused work was carried out (it needs the split-K
 // reduction pass); if not, the caller launches the separate kernel.
 size_t skinny_workspace_bytes(int M, int N, int K);
+void skinny_describe(int M, int N, int K, int* tile_cols, int* splits);  // the plan launch_skinny_gemm follows
 hipError_t launch_skinny_gemm(const void* X, const void* W, int M, int N, int K, const Epilogue& ep,
                               void* workspace, hipStream_t stream, const SkinnyFused* fused = nullptr,
                               bool* fused_done = nullptr);
