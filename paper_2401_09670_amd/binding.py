@@ -59,6 +59,10 @@ def load_library() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
                            "(there is no fallback path)")
+    # torch ships a HIP runtime of its own under the same library name: it has to be the one in the process
+    # before libds.so asks for it, or torch later finds the system's copy loaded in its place (seen as a
+    # segmentation fault at torch's first GPU call when this library was loaded first)
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     lib.ds_create.argtypes = [ctypes.POINTER(ModelCfg), ctypes.POINTER(vp)]

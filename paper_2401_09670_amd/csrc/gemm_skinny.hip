@@ -742,7 +742,7 @@ static hipError_t launch_wring(int nt, const SkinnyParams& p, hipStream_t stream
 // Up to 64 rows it takes both widths; for 65..128 rows only the 80-column one, where a workgroup re-reads 1.6
 // activation bytes per weight byte rather than 2 (measured at 128 rows: FFN-in of OPT-13B / 66B and QKV of
 // OPT-175B 18-27 % faster than the split-K ring kernel, every 64-column shape equal or up to 20 % slower).
-DS_SWITCH(g_skinny_wring, 1);  // 0 = never use the wave-private-ring kernel
+DS_SWITCH(g_skinny_wring, 1);  // 0 = never use the wave-private-ring kernel, 2 = also where it needs several rounds
 static int wring_tiles(int M, int N, int K) {
   if (!g_skinny_wring || M > 128 || K < 256 || K % 256 != 0) return 0;
   const int t4 = (N + 63) / 64, t5 = (N + 79) / 80;
@@ -758,7 +758,7 @@ static int wring_tiles(int M, int N, int K) {
   // OPT-175B 245 -> 214 us, QKV of OPT-66B 107 -> 98 us; QKV of OPT-175B and FFN-in of OPT-66B (two rounds of 80
   // columns against 144 workgroups of 256) stay here, 6-9 % ahead.
   const int rounds = nt == 5 ? r5 : r4;
-  if (rounds > 1 && M > 16) {
+  if (rounds > 1 && M > 16 && g_skinny_wring != 2) {
     const double rows = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
     const double wring_cost = rounds * 256.0 * (16.0 * nt + rows) * K * 2.0;
     double ring_cost;
