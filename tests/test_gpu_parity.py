@@ -142,6 +142,22 @@ def test_linear_skinny_path(gpu, rows, in_f, out_f, bias, relu, residual):
     _linear_case(ctx, rows, in_f, out_f, bias, relu, residual, seed=1000 + rows)
 
 
+def test_linear_wide_products_that_need_several_rounds(gpu):
+    """Few rows against very many output columns: the unsplit kernel would need three rounds of 64-column
+    workgroups, each re-reading the activations, and the plan hands the product to the ring kernel with 256-column
+    tiles; two rounds of 80 columns against a part-filled round of 256-column tiles stay on the unsplit kernel.
+    Both paths against the oracle, and the plan as ds_linear_plan reports it."""
+    ctx = gu.make_ctx(synth.TINY)
+    assert ctx.ds_linear_plan(64, 1024, 49152) == dict(streaming=True, tile_rows=0, tile_cols=256, splits=1,
+                                                        cut_cols=0)
+    assert ctx.ds_linear_plan(64, 1024, 36864) == dict(streaming=True, tile_rows=0, tile_cols=80, splits=1,
+                                                        cut_cols=0)
+    assert ctx.ds_linear_plan(16, 1024, 49152)["tile_cols"] == 64      # 16 activation rows: re-reading them is cheap
+    _linear_case(ctx, 64, 1024, 49152, True, True, False, seed=2001)
+    _linear_case(ctx, 40, 1024, 36864, True, False, False, seed=2002)
+    _linear_case(ctx, 33, 512, 27648, False, False, False, seed=2003)  # 432 workgroups of 64 columns, or 108 x 2 splits
+
+
 # ------------------------------------------------------------------ attention
 @pytest.mark.parametrize("head_dim,n_heads,lens", [
     (64, 4, [1, 5, 64, 129, 300]),

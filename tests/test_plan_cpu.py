@@ -78,3 +78,17 @@ def test_workspace_sized_for_a_maximum_serves_smaller_batches(ctx):
     big = ctx.ds_prefill_workspace_bytes(2048)
     for t in (257, 512, 1000, 1024, 1536, 2047):
         assert ctx.ds_prefill_workspace_bytes(t) <= big
+
+
+def test_wide_decode_products_leave_the_unsplit_kernel_when_it_would_need_several_rounds(ctx):
+    """64 rows: three rounds of 64-column workgroups re-read the activations three times over (OPT-175B FFN-in),
+    two rounds of 64 columns lose to 108 x 2 workgroups of 256 (OPT-66B QKV); two rounds of 80 columns against a
+    part-filled round of 256-column tiles stay (OPT-175B QKV, OPT-66B FFN-in), and so does everything at 16 rows."""
+    assert ctx.ds_linear_plan(64, 12288, 49152) == dict(streaming=True, tile_rows=0, tile_cols=256, splits=1, cut_cols=0)
+    assert ctx.ds_linear_plan(64, 9216, 27648) == dict(streaming=True, tile_rows=0, tile_cols=256, splits=2, cut_cols=0)
+    for k, n in ((12288, 36864), (9216, 36864)):
+        assert ctx.ds_linear_plan(64, k, n)["tile_cols"] == 80
+    for k, n in ((12288, 49152), (9216, 27648)):
+        assert ctx.ds_linear_plan(16, k, n) == dict(streaming=True, tile_rows=0, tile_cols=64, splits=1, cut_cols=0)
+    # the OPT-13B products fit one round unsplit: 64 and 80 columns per workgroup
+    assert ctx.ds_linear_plan(64, 5120, 15360)["tile_cols"] == 64 and ctx.ds_linear_plan(64, 5120, 20480)["tile_cols"] == 80
