@@ -549,7 +549,7 @@ ds_status ds_prefill_attention(ds_ctx* ctx, const void* q, const void* k, const 
     if (ds_status st = validate_cu(ctx, "ds_prefill_attention", cu_seqlens, B, t, max_seqlen, s, cu)) return st;
   }
   DS_LAUNCH(ctx, s, DS_K_PREFILL_ATTN,
-            ds::launch_prefill_attention(q, k, v, cu_seqlens, B, max_seqlen, ctx->cfg.n_heads, ctx->cfg.n_kv_heads,
+            ds::launch_prefill_attention(q, k, v, cu_seqlens, B, t, max_seqlen, ctx->cfg.n_heads, ctx->cfg.n_kv_heads,
                                          ctx->cfg.head_dim, o, s));
   return DS_OK;
 }
@@ -607,7 +607,7 @@ ds_status ds_prefill(ds_ctx* ctx, const ds_layer_weights* w, const void* x, cons
   }
   // o = causal attention per request
   DS_LAUNCH(ctx, s, DS_K_PREFILL_ATTN,
-            ds::launch_prefill_attention(q, k_out, v_out, cu_seqlens, B, max_seqlen, c.n_heads, c.n_kv_heads,
+            ds::launch_prefill_attention(q, k_out, v_out, cu_seqlens, B, t, max_seqlen, c.n_heads, c.n_kv_heads,
                                          c.head_dim, o, s));
   // x1 = x + o W_o^T + b_o
   {

@@ -102,8 +102,9 @@ hipError_t launch_embed(const int32_t* token_ids, const int32_t* positions, cons
 
 // Causal attention within each packed request; q,o rows have `n_heads*head_dim` elements, k,v rows
 // `n_kv_heads*head_dim` (query head j reads key/value head j / (n_heads/n_kv_heads)).
+// `t` = rows in all (sum of the lengths), which only steers the choice of the workgroup order.
 hipError_t launch_prefill_attention(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
-                                    int B, int max_seqlen, int n_heads, int n_kv_heads, int head_dim, void* o,
+                                    int B, int t, int max_seqlen, int n_heads, int n_kv_heads, int head_dim, void* o,
                                     hipStream_t stream);
 
 // contiguous [t,n,s] -> paged [num_blocks,n,16,s] for K and V in one launch

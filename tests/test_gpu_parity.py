@@ -184,6 +184,37 @@ def test_prefill_attention(gpu, head_dim, n_heads, lens):
     assert gu.rel_err(gu.to_f64(o).reshape(t, n_heads, head_dim), ref) < TOL
 
 
+def test_prefill_attention_two_query_tiles_per_workgroup(gpu):
+    """A batch whose K/V (192 MB) no longer fits the last-level cache beside everything else: the launch then runs
+    a pair's workgroups back to back, each taking query tile nq-1-r and then tile r.  Ragged on purpose: an odd
+    tile count (the middle tile has no mirror image), a one-token and a one-tile request between long ones, a
+    last tile of one row.  Sampled rows of every request against the oracle, all 64 heads."""
+    n_heads, head_dim, lens = 64, 128, [3000, 129, 1, 2100, 640]
+    shape = small_shape(head_dim, n_heads)
+    ctx = gu.make_ctx(shape)
+    t, h = sum(lens), shape.hidden
+    assert 4 * t * h > 160e6                      # the size from which the launcher takes this order
+    qb = synth.make_activations(t, h, seed=41)
+    kb = synth.make_activations(t, h, seed=42)
+    vb = synth.make_activations(t, h, seed=43)
+    o = torch.full((t, h), 7.0, dtype=torch.bfloat16, device="cuda")
+    ctx.ds_prefill_attention(gu.to_dev(qb), gu.to_dev(kb), gu.to_dev(vb), gu.i32_dev(synth.cu_seqlens(lens)),
+                             len(lens), t, max(lens), o)
+    torch.cuda.synchronize()
+    got = gu.to_f64(o).reshape(t, n_heads, head_dim)
+    r0 = 0
+    for l in lens:
+        rows = sorted({r for r in (0, 1, 31, 32, 127, 128, 129, 255, 256, 1023, 1024, 1407, 1408, 1535, 1536,
+                                   l // 2, l - 130, l - 129, l - 128, l - 2, l - 1) if 0 <= r < l})
+        sl = slice(r0, r0 + l)
+        q, k, v = (orc.from_bf16_bits(a[sl]).reshape(l, n_heads, head_dim) for a in (qb, kb, vb))
+        ref = orc.attention_rows(q[rows], np.array(rows), k, v)
+        assert gu.rel_err(got[sl][rows], ref) < TOL, l
+        assert gu.rel_err_rows(got[sl][rows].reshape(len(rows) * n_heads, -1), ref.reshape(len(rows) * n_heads, -1)) < 2 * TOL, l
+        r0 += l
+    assert torch.isfinite(o.float()).all()        # every row was written
+
+
 @pytest.mark.parametrize("head_dim,n_heads,kv_lens", [
     (64, 4, [1, 16, 17, 100, 600]),
     (128, 5, [512, 513, 31, 2]),
