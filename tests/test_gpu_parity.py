@@ -184,12 +184,13 @@ def test_prefill_attention(gpu, head_dim, n_heads, lens):
     assert gu.rel_err(gu.to_f64(o).reshape(t, n_heads, head_dim), ref) < TOL
 
 
-def test_prefill_attention_two_query_tiles_per_workgroup(gpu):
+@pytest.mark.parametrize("n_heads,head_dim", [(64, 128), (128, 64)])
+def test_prefill_attention_two_query_tiles_per_workgroup(gpu, n_heads, head_dim):
     """A batch whose K/V (192 MB) no longer fits the last-level cache beside everything else: the launch then runs
     a pair's workgroups back to back, each taking query tile nq-1-r and then tile r.  Ragged on purpose: an odd
     tile count (the middle tile has no mirror image), a one-token and a one-tile request between long ones, a
-    last tile of one row.  Sampled rows of every request against the oracle, all 64 heads."""
-    n_heads, head_dim, lens = 64, 128, [3000, 129, 1, 2100, 640]
+    last tile of one row.  Sampled rows of every request against the oracle, all heads."""
+    lens = [3000, 129, 1, 2100, 640]
     shape = small_shape(head_dim, n_heads)
     ctx = gu.make_ctx(shape)
     t, h = sum(lens), shape.hidden
