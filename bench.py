@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the prefill -> KV hand-off -> decode hot path on one MI355X.
 
-Workload (BASELINE config 2, the shape of the paper's Fig. 1): ONE OPT-13B
+Workload (`opt13b-1layer-in512-out64`, the shape of the paper's Fig. 1): ONE OPT-13B
 layer (h 5120, 40 heads x 128, FFN 20480, bf16).  One "step" serves a batch of
 64 requests with 512 prompt tokens and 64 output tokens each:
   16 x [ ds_prefill(4 prompts x 512) + ds_kv_migrate into the paged cache ]
